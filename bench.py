@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the operator hot path on one MI355X.
+
+One "step" is one pass over the six operator calls of the workload (GMM 512^3, C2D,
+ConvLayer, TBG, DEP, stride-2 C2D; shapes and seeds in paper_2006_06762_amd/inputs.py),
+all inputs resident in HBM.  Prints ONE JSON line:
+
+  value      whole-step fp32 throughput in TFLOP/s (sum of the operators' algorithmic
+             FLOPs / step time), buffers rotated between steps so that a step does not
+             find its inputs in the 256 MB Infinity Cache of the previous one;
+  per_op     every operator's own launch time (HIP events on the launch stream), warm
+             (same buffers) and cold (rotating buffer sets), TFLOP/s against the
+             157.3 TFLOP/s fp32 MFMA peak and GB/s against 8 TB/s;
+  roofline   the dominant kernel (the implicit-GEMM convolution on its largest launch);
+  cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample.
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 2.4 GHz x 256 flop/clk/CU
+PEAK_HBM_GBS = 8000.0
+METRIC = "achieved TFLOP/s and % of fp32 MFMA peak per operator; DEP HBM GB/s"
+
+
+def conv_flops(s):
+    return 2.0 * s.N * s.K * s.OH * s.OW * s.C * s.R * s.S
+
+
+def conv_bytes(s):
+    return 4.0 * (s.N * s.C * s.H * s.W + s.K * s.C * s.R * s.S + s.N * s.K * s.OH * s.OW)
+
+
+def workload_table(I):
+    """Algorithmic FLOPs and compulsory bytes (each tensor once) per operator call."""
+    g, t, d = I.GMM, I.TBG, I.DEP
+    return {
+        "GMM": (2.0 * g.M * g.N * g.K, 4.0 * (g.M * g.K + g.K * g.N + g.M * g.N), "mfma"),
+        "C2D": (conv_flops(I.C2D), conv_bytes(I.C2D), "mfma"),
+        "ConvLayer": (conv_flops(I.CONVLAYER), conv_bytes(I.CONVLAYER) + 4.0 * 4 * I.CONVLAYER.K, "mfma"),
+        "TBG": (2.0 * t.B * t.H * t.S * t.S * t.D, 4.0 * (2 * t.B * t.S * t.H * t.D + t.B * t.H * t.S * t.S),
+                "mfma"),
+        "DEP": (2.0 * d.N * d.C * d.OH * d.OW * 9, 4.0 * (2 * d.N * d.C * d.H * d.W + d.C * 9), "hbm"),
+        "C2D_S2": (conv_flops(I.C2D_S2), conv_bytes(I.C2D_S2), "mfma"),
+    }
+
+
+class OpSet:
+    """Device tensors of one buffer set and the six launches over them."""
+
+    def __init__(self, anr, I, torch, host):
+        self.anr = anr
+        dev = lambda a: torch.from_numpy(a).cuda()
+        self.t = {}
+        for name in I.CONFIG_NAMES:
+            cfg = host[name]
+            self.t[name] = {k: dev(v) for k, v in cfg.items() if isinstance(v, np.ndarray)}
+        e = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+        s = I.C2D
+        self.t["GMM"]["C"] = e(I.GMM.M, I.GMM.N)
+        self.t["C2D"]["y"] = e(s.N, s.K, s.OH, s.OW)
+        s = I.CONVLAYER
+        self.t["ConvLayer"]["y"] = e(s.N, s.K, s.OH, s.OW)
+        self.t["TBG"]["out"] = e(I.TBG.B, I.TBG.H, I.TBG.S, I.TBG.S)
+        s = I.DEP
+        self.t["DEP"]["y"] = e(s.N, s.C, s.OH, s.OW)
+        s = I.C2D_S2
+        self.t["C2D_S2"]["y"] = e(s.N, s.K, s.OH, s.OW)
+        self.I = I
+
+    def run(self, name):
+        a, t, I = self.anr, self.t[name], self.I
+        if name == "GMM":
+            a.gemm(t["A"], t["B"], t["C"])
+        elif name == "C2D":
+            a.conv2d(t["x"], t["w"], t["y"], I.C2D.stride, I.C2D.pad)
+        elif name == "ConvLayer":
+            a.conv_bn_relu(t["x"], t["w"], t["gamma"], t["beta"], t["mean"], t["var"], I.BN_EPS, t["y"],
+                           I.CONVLAYER.stride, I.CONVLAYER.pad)
+        elif name == "TBG":
+            a.tbg(t["q"], t["k"], t["out"])
+        elif name == "DEP":
+            a.dwconv(t["x"], t["w"], t["y"], I.DEP.stride, I.DEP.pad)
+        elif name == "C2D_S2":
+            a.conv2d(t["x"], t["w"], t["y"], I.C2D_S2.stride, I.C2D_S2.pad)
+        else:
+            raise KeyError(name)
+
+    def output(self, name):
+        t = self.t[name]
+        return t.get("y", t.get("C", t.get("out")))
+
+    def step(self):
+        for name in self.I.CONFIG_NAMES:
+            self.run(name)
+
+
+def time_launches(torch, fn, reps):
+    """Average time of one call of fn in microseconds, by HIP events on the launch stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(reps):
+        fn(i)
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) * 1000.0 / reps
+
+
+def oracle_reference(I, host, name):
+    import oracle
+    c = host[name]
+    s = c["shape"]
+    if name == "GMM":
+        return oracle.gemm(c["A"], c["B"])
+    if name in ("C2D", "C2D_S2"):
+        return oracle.conv2d(c["x"], c["w"], s.stride, s.pad)
+    if name == "ConvLayer":
+        return oracle.conv_bn_relu(c["x"], c["w"], c["gamma"], c["beta"], c["mean"], c["var"], c["eps"],
+                                   s.stride, s.pad)
+    if name == "TBG":
+        return oracle.tbg(c["q"], c["k"])
+    if name == "DEP":
+        return oracle.dwconv(c["x"], c["w"], s.stride, s.pad)
+    raise KeyError(name)
+
+
+def cpu_baseline(I, host, table):
+    """Time the fp64 oracle, as it stands, on the host cores: one pass over the whole step
+    (all six operators at full size).  Also returns the references for the parity check."""
+    import oracle
+    cores = oracle.max_threads()
+    refs = {}
+    t0 = time.perf_counter()
+    for name in I.CONFIG_NAMES:
+        refs[name] = oracle_reference(I, host, name)
+    dt = time.perf_counter() - t0
+    flops = sum(table[n][0] for n in I.CONFIG_NAMES)
+    return refs, {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "seconds": dt,
+        "sample": "one full step (all six operator calls at full size, %.2f GFLOP), OpenMP over the "
+                  "outer loop on %d threads" % (flops / 1e9, cores),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle timing and parity check (profiling runs)")
+    ap.add_argument("--only", default=None, help="profiling aid: launch only this operator in the step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU figures are not produced",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2006_06762_amd import binding as anr
+    from paper_2006_06762_amd import inputs as I
+
+    table = workload_table(I)
+    host = {name: I.config_inputs(name) for name in I.CONFIG_NAMES}
+    names = I.CONFIG_NAMES if args.only is None else (args.only,)
+
+    # one step touches ~117 MB; 4 rotating sets keep a step from finding its data in the
+    # 256 MB Infinity Cache, 12 sets do the same for a single small operator
+    NSETS = 12
+    sets = [OpSet(anr, I, torch, host) for _ in range(NSETS)]
+
+    def step(i):
+        s = sets[i % 4]
+        for n in names:
+            s.run(n)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1000.0 / args.steps
+    step_flops = sum(table[n][0] for n in names)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-operator launch times
+    per_op = []
+    for n in names:
+        flops, nbytes, bound = table[n]
+        reps = 200
+        for i in range(10):
+            sets[0].run(n)
+        warm = time_launches(torch, lambda i: sets[0].run(n), reps)
+        cold = time_launches(torch, lambda i: sets[i % NSETS].run(n), reps)
+        rec = {"op": n, "bound": bound, "flops": flops, "bytes": nbytes,
+               "us_warm": warm, "us_cold": cold,
+               "tflops_warm": flops / warm / 1e6, "tflops_cold": flops / cold / 1e6,
+               "gbs_warm": nbytes / warm / 1e3, "gbs_cold": nbytes / cold / 1e3}
+        rec["frac_mfma_peak_warm"] = rec["tflops_warm"] / PEAK_MFMA_F32_TFLOPS
+        rec["frac_mfma_peak_cold"] = rec["tflops_cold"] / PEAK_MFMA_F32_TFLOPS
+        rec["frac_hbm_peak_cold"] = rec["gbs_cold"] / PEAK_HBM_GBS
+        per_op.append(rec)
+
+    by = {r["op"]: r for r in per_op}
+    dom = by.get("C2D_S2") or per_op[0]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dom["op"])
+        except Exception:
+            traffic = None
+    roofline = {
+        "kernel": "conv_igemm_kernel (%s launch)" % dom["op"], "bound": "mfma",
+        "achieved": dom["tflops_cold"], "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+        "frac": dom["tflops_cold"] / PEAK_MFMA_F32_TFLOPS, "traffic": traffic,
+        "launch_us": dom["us_cold"],
+    }
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "one step = GMM 512^3 + C2D N16 64->64 56^2 3x3 + ConvLayer N16 128->128 28^2 "
+                               "3x3+BN+ReLU + TBG B16 S128 H12 D64 + DEP N16 C256 28^2 3x3 + C2D N16 256->512 "
+                               "28^2 3x3 s2 (all BASELINE configs, fp32)" if args.only is None
+                   else "only " + args.only,
+                   "step_gflop": step_flops / 1e9, "buffer_sets_rotated": 4},
+        "roofline": roofline,
+        "peaks": {"mfma_f32_tflops": PEAK_MFMA_F32_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
+        "per_op": per_op,
+    }
+
+    if not args.no_cpu_baseline and args.only is None:
+        refs, base = cpu_baseline(I, host, table)
+        out["cpu_baseline"] = base
+        errs = {}
+        for n in names:
+            sets[0].run(n)
+            got = sets[0].output(n).cpu().numpy().astype(np.float64)
+            errs[n] = float(np.max(np.abs(got - refs[n]) / np.maximum(1.0, np.abs(refs[n]))))
+        out["max_rel_err_vs_oracle"] = errs
+        out["parity_ok"] = all(e <= 1e-4 for e in errs.values())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,166 @@
+/*
+ * anr.h - C ABI of the MI355X (gfx950) fp32 operator library.
+ *
+ * The entry points are the dense fp32 operator programs evaluated in
+ * arXiv 2006.06762 ("Ansor"): GMM, C2D and DEP of the single-operator
+ * benchmark (Sec. 7.1, shapes in Appendix C) and the ConvLayer and TBS
+ * subgraphs (Sec. 7.2).  All arithmetic is fp32 in, fp32 accumulate, fp32 out
+ * (Sec. 7: float32 is used for all evaluations).
+ *
+ * Conventions common to every call
+ *   - Every tensor pointer is DEVICE memory owned by the caller.  The library
+ *     never allocates, frees or synchronises.  Work is enqueued on the HIP
+ *     stream passed as `hip_stream` (a hipStream_t cast to void*; NULL is the
+ *     default stream) and the call returns without waiting for it.
+ *   - Descriptors are HOST structs, read during the call only.
+ *   - Inputs are read-only; outputs are fully overwritten (no accumulate) and
+ *     must not overlap any input.
+ *   - Pointers must be 4-byte aligned.  16-byte aligned pointers together
+ *     with row extents/strides that are multiples of 4 elements select the
+ *     vectorised kernels; anything else runs a slower kernel with the same
+ *     results.
+ *   - `ws`/`ws_bytes` is an optional device workspace.  anr_workspace_size()
+ *     says how many bytes an operation wants (0 for every operation in this
+ *     version); ws may be NULL when that is 0.
+ *   - Errors are return codes.  All argument checks happen on the host before
+ *     anything is launched, so an invalid call has no effect on the device.
+ *   - Thread-safe and re-entrant: there is no mutable global state.
+ */
+#ifndef ANR_H
+#define ANR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ANR_OK = 0,
+    ANR_ERR_NULL = 1,         /* a required pointer is NULL                        */
+    ANR_ERR_INVALID_ARG = 2,  /* non-positive extent, bad stride, empty output ... */
+    ANR_ERR_UNSUPPORTED = 3,  /* valid but not implemented (dilation, layout)      */
+    ANR_ERR_WORKSPACE = 4,    /* ws_bytes smaller than anr_workspace_size()        */
+    ANR_ERR_LAUNCH = 5        /* the HIP runtime refused the launch                */
+} anr_status;
+
+typedef enum { ANR_LAYOUT_NCHW = 0 } anr_layout;
+
+typedef enum {
+    ANR_OP_GEMM = 0, ANR_OP_CONV2D = 1, ANR_OP_CONV_BN_RELU = 2, ANR_OP_DWCONV = 3,
+    ANR_OP_TBG = 4, ANR_OP_TBS = 5
+} anr_op;
+
+/*
+ * GMM.  C[b] = A[b] (M x K) . B[b] (K x N), b = 0 .. batch-1; all row-major.
+ * Element (i,k) of A[b] is A[b*strideA + i*lda + k]; likewise B (ldb) and C
+ * (ldc).  Requirements: M,N,K,batch >= 1; lda >= K; ldb >= N; ldc >= N;
+ * for batch > 1, strideC >= (M-1)*ldc + N (outputs must not overlap);
+ * strideA/strideB may be 0 to share an operand across the batch.
+ */
+typedef struct {
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int64_t batch;
+    int64_t strideA, strideB, strideC;
+} anr_gemm_desc;
+
+/*
+ * Convolution geometry shared by C2D, ConvLayer and DEP.
+ *   x [N,C,H,W], y [N,K,OH,OW] with OH = floor((H + 2*pad_h - R)/stride_h) + 1
+ *   (OW alike).  Cross-correlation (no kernel flip); zero padding, the same
+ *   amount on both sides.  K is the number of output channels; for the
+ *   depthwise call K must equal C (channel multiplier 1).
+ *   Weights are always packed: OIHW [K,C,R,S] for conv2d / conv_bn_relu,
+ *   [C,1,R,S] for dwconv.
+ *   x_stride / y_stride are element strides for (n, c, h, w).  All four zero
+ *   means packed NCHW.  Otherwise every stride must be >= 1 and the view must
+ *   not alias itself (w-stride 1 is required by this version: anything else
+ *   returns ANR_ERR_UNSUPPORTED).
+ *   dil_h, dil_w must be 1 and layout must be ANR_LAYOUT_NCHW (else
+ *   ANR_ERR_UNSUPPORTED).  pad >= 0, stride >= 1, pad < kernel extent is NOT
+ *   required.  OH <= 0 or OW <= 0 is ANR_ERR_INVALID_ARG.
+ */
+typedef struct {
+    int32_t N, C, H, W;
+    int32_t K, R, S;
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    int32_t dil_h, dil_w;
+    int32_t layout;
+    int64_t x_stride[4];
+    int64_t y_stride[4];
+} anr_conv_desc;
+
+/*
+ * TBG / TBS.  q and k are indexed [b, s, h, d] (B x S x H x D), out is
+ * indexed [b, h, i, j] (B x H x S x S).  Strides are in elements; all four
+ * zero means packed in that index order.  The d-stride of q and k and the
+ * j-stride of out must be 1 in this version.
+ */
+typedef struct {
+    int32_t B, S, H, D;
+    int64_t q_stride[4];
+    int64_t k_stride[4];
+    int64_t o_stride[4];
+} anr_tbg_desc;
+
+/* GMM (Sec. 4.1: C(i,j) = sum_k A[i,k] * B[k,j]; benchmark shapes in
+ * Appendix C "GMM"). */
+anr_status anr_gemm(const anr_gemm_desc *desc, const float *A, const float *B, float *C,
+                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/* C2D (Sec. 7.1, Appendix C "C2D"): y[n,k,oh,ow] = sum_{c,r,s}
+ * x[n,c,oh*stride_h-pad_h+r, ow*stride_w-pad_w+s] * w[k,c,r,s], taps outside
+ * the image contributing zero. */
+anr_status anr_conv2d(const anr_conv_desc *desc, const float *x, const float *w, float *y,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ConvLayer (Sec. 7.2): the convolution above, then inference batch
+ * normalisation per output channel, gamma*(v-mean)/sqrt(var+eps)+beta, then
+ * ReLU, in one kernel (Table 1 rule 4: element-wise consumers are fused into
+ * the tiled producer).  gamma, beta, mean, var: K device floats each.
+ * eps must be finite and var[k]+eps > 0 is the caller's responsibility. */
+anr_status anr_conv_bn_relu(const anr_conv_desc *desc, const float *x, const float *w,
+                            const float *gamma, const float *beta,
+                            const float *mean, const float *var, float eps,
+                            float *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* DEP (Sec. 7.1, Appendix C "DEP"): depthwise convolution, multiplier 1:
+ * y[n,c,oh,ow] = sum_{r,s} x[n,c,ih,iw] * w[c,0,r,s]. */
+anr_status anr_dwconv(const anr_conv_desc *desc, const float *x, const float *w, float *y,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* TBS without the softmax (Sec. 7.2: two transposes and one batch matmul of
+ * multi-head attention): out[b,h,i,j] = sum_d q[b,i,h,d] * k[b,j,h,d].  The
+ * transposes [B,S,H,D] -> [B,H,S,D] are folded into the addressing; no
+ * 1/sqrt(D) scaling. */
+anr_status anr_tbg(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Full TBS (Sec. 7.2, Appendix C "TBS"): anr_tbg followed by a softmax over j,
+ * fused in the same kernel.  Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
+anr_status anr_tbs(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Bytes of device workspace `op` (an anr_op) wants for `desc` (the matching
+ * descriptor type).  Writes 0 when none is needed.  Validates the descriptor
+ * the same way the operation does. */
+anr_status anr_workspace_size(int op, const void *desc, size_t *bytes);
+
+/* Static, NUL-terminated description of a status code. */
+const char *anr_status_string(anr_status status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int anr_version(void);
+
+/* Diagnostics for ANR_ERR_LAUNCH: the hipError_t value (and its runtime description) of
+ * the most recent launch that failed in the calling thread; 0 if none has. */
+int anr_last_hip_error(void);
+const char *anr_last_hip_error_string(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANR_H */

@@ -4,14 +4,18 @@
 HIP library; everything else is the ctypes binding of ``libanr.so`` and is
 loaded on first use.  If the library has not been built, that first use raises.
 """
-from . import inputs  # noqa: F401
+import importlib
 
-_BINDING_NAMES = None
+from . import inputs  # noqa: F401
 
 
 def __getattr__(name):
     # Lazy: keep `import paper_2006_06762_amd.inputs` free of the HIP library.
-    from . import binding
+    if name.startswith("__"):
+        raise AttributeError(name)
+    binding = importlib.import_module(__name__ + ".binding")
+    if name == "binding":
+        return binding
     if hasattr(binding, name):
         return getattr(binding, name)
     raise AttributeError("module %r has no attribute %r" % (__name__, name))

@@ -1,0 +1,46 @@
+// Device-side helpers shared by the HIP kernels (gfx950 / CDNA4, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace anr {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// v_mfma_f32_32x32x2_f32: D(32x32) += A(32x2) * B(2x32), fp32 throughout.
+// Lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32].
+// Register r of lane l holds D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32].
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// v_mfma_f32_16x16x4_f32: D(16x16) += A(16x4) * B(4x16).
+// Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16].
+// Register r of lane l holds D[i = 4*(l/16) + r][j = l%16].
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x4 ldg4(const float* p)
+{
+    return *reinterpret_cast<const f32x4*>(p);
+}
+
+__device__ __forceinline__ void stg4(float* p, f32x4 v)
+{
+    *reinterpret_cast<f32x4*>(p) = v;
+}
+
+__device__ __forceinline__ f32x4 zero4()
+{
+    f32x4 z = {0.f, 0.f, 0.f, 0.f};
+    return z;
+}
+
+}  // namespace anr

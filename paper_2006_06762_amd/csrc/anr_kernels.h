@@ -1,0 +1,62 @@
+// Internal launch interface between the C-ABI layer (api.cpp) and the kernel
+// translation units.  Every launcher enqueues on `stream` and returns the
+// hipError_t of the launch; none of them allocates or synchronises.  The
+// arguments have been validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace anr {
+
+template <typename T>
+struct NonDeduced {
+    using type = T;
+};
+
+// Launch with the status returned by the launch call itself (hipGetLastError would also
+// report, and clear, errors left behind by other users of the runtime in this thread).
+template <typename... KArgs>
+inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes,
+                                hipStream_t stream, typename NonDeduced<KArgs>::type... args)
+{
+    void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, lds_bytes, stream);
+}
+
+// Batched C = A.B (B_IS_NK false: B is K x N, row stride ldb) or C = A.B^T
+// (B_IS_NK true: B is N x K, row stride ldb).  Batch index z in [0, batch) is
+// split as z = zo*batch_inner + zi, and operand X starts at
+// X + zo*sXo + zi*sXi.
+struct GemmArgs {
+    const float* A;
+    const float* B;
+    float* C;
+    int M, N, K;
+    int64_t lda, ldb, ldc;
+    int batch, batch_inner;
+    int64_t sAo, sAi, sBo, sBi, sCo, sCi;
+    bool b_is_nk;
+    bool softmax_rows;   // TBS: softmax over each output row (requires N <= 1024)
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+
+struct ConvArgs {
+    const float* x;
+    const float* w;
+    float* y;
+    int N, C, H, W, K, R, S;
+    int stride_h, stride_w, pad_h, pad_w;
+    int OH, OW;
+    int64_t xs[4];   // element strides n,c,h,w (w stride is 1)
+    int64_t ys[4];
+    // fused epilogue (ConvLayer): nullptr gamma means plain convolution
+    const float* gamma;
+    const float* beta;
+    const float* mean;
+    const float* var;
+    float eps;
+};
+hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream);
+hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
+
+}  // namespace anr

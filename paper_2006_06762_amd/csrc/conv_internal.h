@@ -1,0 +1,19 @@
+// Launchers private to the convolution translation units.
+#pragma once
+#include "anr_kernels.h"
+
+namespace anr {
+
+hipError_t launch_conv2d_direct(const ConvArgs& a, hipStream_t stream);
+hipError_t launch_dwconv_direct(const ConvArgs& a, hipStream_t stream);
+
+// Implicit-GEMM MFMA convolution.  Returns false in *taken when the geometry is
+// outside what the kernel supports (the caller then uses the direct kernel).
+hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken);
+
+// Register-sliding 3x3 / stride 1 / pad 1 depthwise kernel; same contract.
+hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken);
+
+inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace anr

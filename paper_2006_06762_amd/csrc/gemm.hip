@@ -1,0 +1,297 @@
+// fp32 GEMM on the MFMA units of gfx950: the GMM operator (C = A.B, Sec. 4.1 of
+// arXiv 2006.06762) and the batch matmul of the TBS subgraph (Sec. 7.2) in its
+// A.B^T form.
+//
+// Work-group tile BM x BN, 256 threads = 4 waves in a 2 x 2 grid; every wave
+// owns a (BM/2) x (BN/2) block of C as 32x32 MFMA accumulators.  Operand tiles
+// go HBM/L2 -> registers -> LDS (double buffered, one barrier per K step), and
+// LDS -> registers with 16-byte reads: the 32x32x2 MFMA takes, from lane l,
+// A[l%32][k] for one k chosen by l/32, and the order in which the k values of a
+// tile are fed is free as long as A and B agree, so each half-wave reads four
+// consecutive k of "its" row with one ds_read_b128 and spends them on four MFMAs.
+#include "anr_device.h"
+#include "anr_kernels.h"
+
+namespace anr {
+namespace {
+
+template <int BM, int BN, int BK, bool NT, bool VEC>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs p)
+{
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int MB = WM / 32, NB = WN / 32;
+    constexpr int LDA_S = BK + 4;
+    constexpr int LDB_S = NT ? (BK + 4) : (BN + 4);
+    constexpr int A_TILE = BM * LDA_S;
+    constexpr int B_TILE = NT ? BN * LDB_S : BK * LDB_S;
+    constexpr int KQ = BK / 4;                 // float4 per tile row of A (and of B when NT)
+    constexpr int NQ = BN / 4;                 // float4 per tile row of B when NN
+    constexpr int NA = BM * KQ / 256;
+    constexpr int NBU = (NT ? BN * KQ : BK * NQ) / 256;
+    static_assert(NA >= 1 && NBU >= 1, "tile too small for 256 threads");
+
+    __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
+    __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int bm0 = blockIdx.y * BM, bn0 = blockIdx.x * BN;
+    const int zo = blockIdx.z / p.batch_inner, zi = blockIdx.z % p.batch_inner;
+    const float* __restrict__ A = p.A + zo * p.sAo + zi * p.sAi;
+    const float* __restrict__ B = p.B + zo * p.sBo + zi * p.sBi;
+    float* __restrict__ C = p.C + zo * p.sCo + zi * p.sCi;
+    const int M = p.M, N = p.N, K = p.K;
+
+    f32x4 ra[NA], rb[NBU];
+
+    // tile rows are matrix rows, k contiguous (A always; B when NT)
+    auto load_rows = [&](const float* __restrict__ base, int64_t ld, int row0, int rows_total,
+                         int kt, auto& reg) {
+        constexpr int count = sizeof(reg) / sizeof(f32x4);
+#pragma unroll
+        for (int i = 0; i < count; ++i) {
+            const int u = tid + i * 256;
+            const int row = u / KQ, kq = u % KQ;
+            const int gr = row0 + row, gk = kt * BK + kq * 4;
+            f32x4 v = zero4();
+            if (gr < rows_total) {
+                const float* src = base + (int64_t)gr * ld + gk;
+                if (VEC) {
+                    if (gk < K) v = ldg4(src);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (gk + c < K) v[c] = src[c];
+                }
+            }
+            reg[i] = v;
+        }
+    };
+    auto store_rows = [&](float* tile, int ld_s, const auto& reg) {
+        constexpr int count = sizeof(reg) / sizeof(f32x4);
+#pragma unroll
+        for (int i = 0; i < count; ++i) {
+            const int u = tid + i * 256;
+            const int row = u / KQ, kq = u % KQ;
+            *reinterpret_cast<f32x4*>(&tile[row * ld_s + kq * 4]) = reg[i];
+        }
+    };
+    auto load_b_nn = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < NBU; ++i) {
+            const int u = tid + i * 256;
+            const int k = u / NQ, nq = u % NQ;
+            const int gk = kt * BK + k, gn = bn0 + nq * 4;
+            f32x4 v = zero4();
+            if (gk < K) {
+                const float* src = B + (int64_t)gk * p.ldb + gn;
+                if (VEC) {
+                    if (gn < N) v = ldg4(src);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (gn + c < N) v[c] = src[c];
+                }
+            }
+            rb[i] = v;
+        }
+    };
+    auto store_b_nn = [&](float* tile) {
+#pragma unroll
+        for (int i = 0; i < NBU; ++i) {
+            const int u = tid + i * 256;
+            const int k = u / NQ, nq = u % NQ;
+            *reinterpret_cast<f32x4*>(&tile[k * LDB_S + nq * 4]) = rb[i];
+        }
+    };
+    auto load_tiles = [&](int kt) {
+        load_rows(A, p.lda, bm0, M, kt, ra);
+        if (NT) load_rows(B, p.ldb, bn0, N, kt, rb);
+        else load_b_nn(kt);
+    };
+    auto store_tiles = [&](int buf) {
+        store_rows(As[buf], LDA_S, ra);
+        if (NT) store_rows(Bs[buf], LDB_S, rb);
+        else store_b_nn(Bs[buf]);
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    const int nk = (K + BK - 1) / BK;
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_tiles(kt + 1);
+
+        const float* as = As[buf];
+        const float* bs = Bs[buf];
+#pragma unroll
+        for (int kk = 0; kk < BK / 8; ++kk) {
+            f32x4 a[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                a[mb] = *reinterpret_cast<const f32x4*>(&as[(wm0 + mb * 32 + r32) * LDA_S + kk * 8 + 4 * h]);
+            if (NT) {
+                f32x4 b[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    b[nb] = *reinterpret_cast<const f32x4*>(&bs[(wn0 + nb * 32 + r32) * LDB_S + kk * 8 + 4 * h]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb] = mfma32(a[mb][j], b[nb][j], acc[mb][nb]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float* brow = &bs[(kk * 8 + 4 * h + j) * LDB_S + wn0 + NB * r32];
+                    float b[NB];
+                    if (NB == 2) {
+                        const f32x2 t = *reinterpret_cast<const f32x2*>(brow);
+                        b[0] = t[0];
+                        b[NB - 1] = t[1];
+                    } else {
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) b[nb] = brow[nb];
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb] = mfma32(a[mb][j], b[nb], acc[mb][nb]);
+                }
+            }
+        }
+
+        if (kt + 1 < nk) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Epilogue.  Register r of a 32x32 accumulator is row 8*(r/4) + 4*h + r%4, column r32
+    // of the block; when NN, block nb holds the columns NB*r32 + nb of the wave's strip.
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = bm0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (row >= M) continue;
+            float* crow = C + (int64_t)row * p.ldc;
+            if (NT) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int col = bn0 + wn0 + nb * 32 + r32;
+                    if (col < N) crow[col] = acc[mb][nb][r];
+                }
+            } else {
+                const int col = bn0 + wn0 + NB * r32;
+                if (VEC && NB == 2) {
+                    if (col < N) {
+                        f32x2 v = {acc[mb][0][r], acc[mb][NB - 1][r]};
+                        *reinterpret_cast<f32x2*>(crow + col) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        if (col + nb < N) crow[col + nb] = acc[mb][nb][r];
+                }
+            }
+        }
+    }
+}
+
+// Row softmax in place (TBS): one wave per row of length n <= 1024.
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* out, int64_t rows, int n,
+                                                           int rows_per_mat, int mats_inner,
+                                                           int64_t s_o, int64_t s_i, int64_t ld)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int64_t mat = row / rows_per_mat;
+    const int i = (int)(row % rows_per_mat);
+    float* v = out + (mat / mats_inner) * s_o + (mat % mats_inner) * s_i + (int64_t)i * ld;
+    float x[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int j = lane + t * 64;
+        x[t] = j < n ? v[j] : -INFINITY;
+        mx = fmaxf(mx, x[t]);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int j = lane + t * 64;
+        x[t] = j < n ? expf(x[t] - mx) : 0.f;
+        sum += x[t];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int j = lane + t * 64;
+        if (j < n) v[j] = x[t] * inv;
+    }
+}
+
+template <int BM, int BN, int BK, bool NT, bool VEC>
+hipError_t launch_variant(const GemmArgs& a, hipStream_t stream)
+{
+    dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, a.batch);
+    return launch_kernel(gemm_kernel<BM, BN, BK, NT, VEC>, grid, dim3(256), 0, stream, a);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
+{
+    const bool strides4 = (a.sAo % 4 == 0) && (a.sAi % 4 == 0) && (a.sBo % 4 == 0) &&
+                          (a.sBi % 4 == 0) && (a.sCo % 4 == 0) && (a.sCi % 4 == 0);
+    bool vec = aligned16(a.A) && aligned16(a.B) && aligned16(a.C) && strides4 &&
+               (a.K % 4 == 0) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) && (a.ldc % 4 == 0);
+    if (!a.b_is_nk) vec = vec && (a.N % 4 == 0);
+
+    const int64_t tiles128 = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
+    const bool big = tiles128 >= 192;   // enough 128x128 tiles to occupy most of the 256 CUs
+
+    hipError_t err;
+    if (a.b_is_nk) {
+        if (big) err = vec ? launch_variant<128, 128, 16, true, true>(a, stream)
+                           : launch_variant<128, 128, 16, true, false>(a, stream);
+        else     err = vec ? launch_variant<64, 64, 16, true, true>(a, stream)
+                           : launch_variant<64, 64, 16, true, false>(a, stream);
+    } else {
+        if (big) err = vec ? launch_variant<128, 128, 16, false, true>(a, stream)
+                           : launch_variant<128, 128, 16, false, false>(a, stream);
+        else     err = vec ? launch_variant<64, 64, 16, false, true>(a, stream)
+                           : launch_variant<64, 64, 16, false, false>(a, stream);
+    }
+    if (err != hipSuccess) return err;
+
+    if (a.softmax_rows) {
+        const int64_t rows = (int64_t)a.batch * a.M;
+        err = launch_kernel(softmax_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
+                            a.C, rows, a.N, a.M, a.batch_inner, a.sCo, a.sCi, a.ldc);
+    }
+    return err;
+}
+
+}  // namespace anr

@@ -1,0 +1,171 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, its
+descriptor structs have the layout the binding assumes, and every argument error is
+reported as a return code before anything could be launched (no GPU is touched)."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2006_06762_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "anr.h")
+DUMMY = ctypes.c_void_p(0x1000)       # never dereferenced: validation fails first
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(anr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.raw()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert B.version() >= 100
+    seen = {B.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert "unknown" in B.status_string(99)
+
+
+def test_struct_layout_matches_c(tmp_path):
+    # compile a tiny C program against the header and compare sizeof/offsetof with ctypes
+    src = tmp_path / "layout.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "anr.h"
+int main(void) {
+  printf("%zu %zu %zu\n", sizeof(anr_gemm_desc), sizeof(anr_conv_desc), sizeof(anr_tbg_desc));
+  printf("%zu %zu %zu %zu\n", offsetof(anr_gemm_desc, strideC), offsetof(anr_conv_desc, layout),
+         offsetof(anr_conv_desc, x_stride), offsetof(anr_conv_desc, y_stride));
+  printf("%zu %zu %zu\n", offsetof(anr_tbg_desc, q_stride), offsetof(anr_tbg_desc, k_stride),
+         offsetof(anr_tbg_desc, o_stride));
+  return 0; }''')
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    got = [int(v) for v in out]
+    exp = [ctypes.sizeof(B.GemmDesc), ctypes.sizeof(B.ConvDesc), ctypes.sizeof(B.TbgDesc),
+           B.GemmDesc.strideC.offset, B.ConvDesc.layout.offset, B.ConvDesc.x_stride.offset,
+           B.ConvDesc.y_stride.offset, B.TbgDesc.q_stride.offset, B.TbgDesc.k_stride.offset,
+           B.TbgDesc.o_stride.offset]
+    assert got == exp
+
+
+def gemm_status(**kw):
+    base = dict(M=4, N=4, K=4, lda=4, ldb=4, ldc=4, batch=1, strideA=0, strideB=0, strideC=0)
+    base.update(kw)
+    d = B.GemmDesc(**base)
+    return B.raw().anr_gemm(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None)
+
+
+def test_gemm_validation():
+    assert gemm_status(M=0) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(N=-1) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(K=0) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(batch=0) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(lda=3) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(ldb=3) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(ldc=3) == B.ANR_ERR_INVALID_ARG
+    assert gemm_status(batch=2, strideC=15) == B.ANR_ERR_INVALID_ARG     # overlapping outputs
+    assert gemm_status(batch=70000, strideC=16) == B.ANR_ERR_UNSUPPORTED
+    d = B.GemmDesc(4, 4, 4, 4, 4, 4, 1, 0, 0, 0)
+    lib = B.raw()
+    assert lib.anr_gemm(None, DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_gemm(ctypes.byref(d), None, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_gemm(ctypes.byref(d), DUMMY, None, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_gemm(ctypes.byref(d), DUMMY, DUMMY, None, None, 0, None) == B.ANR_ERR_NULL
+
+
+def conv_status(fn="anr_conv2d", x_stride=None, y_stride=None, **kw):
+    base = dict(N=1, C=4, H=8, W=8, K=4, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1,
+                dil_h=1, dil_w=1, layout=0)
+    base.update(kw)
+    d = B.ConvDesc(**base)
+    if x_stride:
+        d.x_stride = (ctypes.c_int64 * 4)(*x_stride)
+    if y_stride:
+        d.y_stride = (ctypes.c_int64 * 4)(*y_stride)
+    lib = B.raw()
+    if fn == "anr_conv_bn_relu":
+        return lib.anr_conv_bn_relu(ctypes.byref(d), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+                                    ctypes.c_float(1e-5), DUMMY, None, 0, None)
+    return getattr(lib, fn)(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None)
+
+
+@pytest.mark.parametrize("fn", ["anr_conv2d", "anr_conv_bn_relu", "anr_dwconv"])
+def test_conv_validation(fn):
+    for field in ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w"):
+        assert conv_status(fn, **{field: 0}) == B.ANR_ERR_INVALID_ARG, field
+    assert conv_status(fn, pad_h=-1) == B.ANR_ERR_INVALID_ARG
+    assert conv_status(fn, dil_w=0) == B.ANR_ERR_INVALID_ARG
+    assert conv_status(fn, dil_h=2) == B.ANR_ERR_UNSUPPORTED
+    assert conv_status(fn, layout=1) == B.ANR_ERR_UNSUPPORTED
+    assert conv_status(fn, H=2, R=5, pad_h=1) == B.ANR_ERR_INVALID_ARG          # empty output
+    assert conv_status(fn, x_stride=(256, 64, 8, 2)) == B.ANR_ERR_UNSUPPORTED   # w stride != 1
+    assert conv_status(fn, x_stride=(256, 64, 7, 1)) == B.ANR_ERR_INVALID_ARG   # rows overlap
+    assert conv_status(fn, x_stride=(256, 60, 8, 1)) == B.ANR_ERR_INVALID_ARG   # planes overlap
+    assert conv_status(fn, x_stride=(255, 64, 8, 1)) == B.ANR_ERR_INVALID_ARG   # images overlap
+    assert conv_status(fn, y_stride=(256, 64, 8, -1)) == B.ANR_ERR_INVALID_ARG
+
+
+def test_dwconv_requires_k_equals_c():
+    assert conv_status("anr_dwconv", K=8) == B.ANR_ERR_INVALID_ARG
+
+
+def test_conv_null_pointers():
+    d = B.conv_desc((1, 4, 8, 8), 4, 3, 3, (1, 1), (1, 1))
+    lib = B.raw()
+    assert lib.anr_conv2d(None, DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d(ctypes.byref(d), None, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_dwconv(ctypes.byref(d), DUMMY, None, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv_bn_relu(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, DUMMY, DUMMY,
+                                ctypes.c_float(1e-5), DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv_bn_relu(ctypes.byref(d), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+                                ctypes.c_float(float("nan")), DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("fn", ["anr_tbg", "anr_tbs"])
+def test_tbg_validation(fn):
+    lib = B.raw()
+    f = getattr(lib, fn)
+    for field in ("B", "S", "H", "D"):
+        kw = dict(B=1, S=4, H=2, D=4)
+        kw[field] = 0
+        d = B.TbgDesc(**kw)
+        assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+    d = B.TbgDesc(1, 4, 2, 4)
+    assert f(None, DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert f(ctypes.byref(d), DUMMY, DUMMY, None, None, 0, None) == B.ANR_ERR_NULL
+    d.q_stride = (ctypes.c_int64 * 4)(32, 8, 4, 2)
+    assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
+    d = B.TbgDesc(1, 4, 2, 4)
+    d.o_stride = (ctypes.c_int64 * 4)(32, 16, 3, 1)       # rows overlap
+    assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+    if fn == "anr_tbs":
+        d = B.TbgDesc(1, 2048, 1, 4)
+        assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
+
+
+def test_workspace_size():
+    g = B.GemmDesc(512, 512, 512, 512, 512, 512, 1, 0, 0, 0)
+    assert B.workspace_size(B.ANR_OP_GEMM, g) == 0
+    c = B.conv_desc((16, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1))
+    assert B.workspace_size(B.ANR_OP_CONV2D, c) == 0
+    assert B.workspace_size(B.ANR_OP_CONV_BN_RELU, c) == 0
+    assert B.workspace_size(B.ANR_OP_TBG, B.TbgDesc(16, 128, 12, 64)) == 0
+    with pytest.raises(B.AnrError):
+        B.workspace_size(B.ANR_OP_DWCONV, c.__class__(1, 4, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 0))
+    with pytest.raises(B.AnrError):
+        B.workspace_size(42, g)
+    n = ctypes.c_size_t(0)
+    assert B.raw().anr_workspace_size(0, None, ctypes.byref(n)) == B.ANR_ERR_NULL

@@ -1,0 +1,444 @@
+"""GPU parity: every C-ABI entry point against the fp64 CPU oracle, element by element,
+on the same seeded fp32 inputs.
+
+Bar (floating point): max_e |gpu_e - oracle_e| / max(1, |oracle_e|) <= 1e-4.
+Bar (index / layout handling): with small-integer inputs every partial sum is exact in
+fp32, so the GPU result must equal the oracle bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2006_06762_amd import inputs as I
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+CANARY = 12345.0
+
+
+@pytest.fixture(scope="module")
+def anr():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2006_06762_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_err(got, ref):
+    got = got.astype(np.float64)
+    return float(np.max(np.abs(got - ref) / np.maximum(1.0, np.abs(ref))))
+
+
+def guarded(shape):
+    """Output tensor with a canary band before and after it (catches out-of-bounds stores)."""
+    n = int(np.prod(shape))
+    buf = torch.full((n + 2 * 64,), CANARY, dtype=torch.float32, device="cuda")
+    return buf, buf[64:64 + n].view(*shape)
+
+
+def check_guard(buf):
+    torch.cuda.synchronize()
+    assert bool((buf[:64] == CANARY).all()) and bool((buf[-64:] == CANARY).all()), "store out of bounds"
+
+
+def assert_parity(got_t, ref, exact=False, what=""):
+    got = got_t.cpu().numpy()
+    assert not np.isnan(got).any(), what + ": NaN in output"
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), what + ": not bit-exact"
+    else:
+        e = rel_err(got, ref)
+        assert e <= TOL, "%s: rel err %.3e" % (what, e)
+
+
+# ------------------------------------------------------------------ GEMM
+GEMM_SHAPES = [(1, 1, 1), (5, 7, 3), (33, 17, 65), (64, 64, 64), (100, 132, 72), (257, 129, 33),
+               (128, 128, 128), (512, 32, 512), (130, 260, 16)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("ints", [False, True])
+def test_gemm_small(anr, M, N, K, ints):
+    A, B = I.gemm_inputs(I.GemmShape(M, N, K), 100 + M, ints=ints)
+    buf, C = guarded((M, N))
+    anr.gemm(dev(A), dev(B), C)
+    check_guard(buf)
+    assert_parity(C, oracle.gemm(A, B), exact=ints, what="gemm %dx%dx%d" % (M, N, K))
+
+
+def test_gemm_config_512(anr):
+    cfg = I.config_inputs("GMM")
+    C = torch.empty((512, 512), dtype=torch.float32, device="cuda")
+    anr.gemm(dev(cfg["A"]), dev(cfg["B"]), C)
+    assert_parity(C, oracle.gemm(cfg["A"], cfg["B"]), what="GMM 512^3")
+
+
+def test_gemm_1024_and_big_tiles(anr):
+    # large enough for the 128x128 tile variant; ragged in M and N
+    for (M, N, K) in [(1024, 1024, 1024), (1920, 1670, 96)]:
+        A, B = I.gemm_inputs(I.GemmShape(M, N, K), 7)
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        anr.gemm(dev(A), dev(B), C)
+        assert_parity(C, oracle.gemm(A, B), what="gemm %dx%dx%d" % (M, N, K))
+
+
+def test_gemm_batched_and_strided(anr):
+    A, B = I.gemm_inputs(I.GemmShape(70, 52, 40, batch=3), 8)
+    C = torch.empty((3, 70, 52), dtype=torch.float32, device="cuda")
+    anr.gemm(dev(A), dev(B), C)
+    assert_parity(C, oracle.gemm(A, B), what="batched gemm")
+    # leading dimensions larger than the row length (views into wider matrices), odd offsets
+    Aw = torch.zeros((70, 47), device="cuda")
+    Bw = torch.zeros((40, 59), device="cuda")
+    Cw = torch.full((70, 61), CANARY, device="cuda")
+    Aw[:, 3:43] = dev(A[0])
+    Bw[:, 5:57] = dev(B[0])
+    anr.gemm(Aw[:, 3:43], Bw[:, 5:57], Cw[:, 2:54])
+    assert_parity(Cw[:, 2:54].contiguous(), oracle.gemm(A[0], B[0]), what="strided gemm")
+    assert bool((Cw[:, :2] == CANARY).all()) and bool((Cw[:, 54:] == CANARY).all())
+
+
+def test_gemm_identity_returns_a(anr):
+    A, _ = I.gemm_inputs(I.GemmShape(96, 96, 96), 9)
+    C = torch.empty((96, 96), device="cuda")
+    anr.gemm(dev(A), torch.eye(96, device="cuda"), C)
+    assert np.array_equal(C.cpu().numpy(), A)
+
+
+# ------------------------------------------------------------------ conv2d
+# MFMA path: 3x3, W % 4 == 0, C % 8 == 0.  Ragged pixel tiles, K not a multiple of the
+# channel tile, tiles that straddle images, stride 2.
+CONV_FAST = [
+    I.ConvShape(1, 8, 8, 8, 16, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(3, 16, 12, 20, 40, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 8, 28, 28, 70, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(5, 24, 9, 12, 33, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(3, 16, 28, 28, 64, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(2, 8, 17, 16, 20, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 1), (0, 0)),
+    I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 2), (2, 1)),
+    I.ConvShape(1, 32, 56, 56, 64, 3, 3, (1, 1), (1, 1)),
+]
+# everything else goes through the direct kernel
+CONV_GENERIC = [
+    I.ConvShape(2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 3, 30, 30, 8, 7, 7, (2, 2), (3, 3)),
+    I.ConvShape(2, 16, 14, 14, 12, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(2, 16, 14, 14, 12, 1, 1, (2, 2), (0, 0)),
+    I.ConvShape(1, 12, 7, 7, 9, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 2, 6, 8, 2, 3, 2, (2, 1), (0, 1)),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_FAST + CONV_GENERIC, ids=str)
+@pytest.mark.parametrize("ints", [False, True])
+def test_conv2d_small(anr, shape, ints):
+    x, w = I.conv_inputs(shape, 200, ints=ints)
+    buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
+    anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad)
+    check_guard(buf)
+    assert_parity(y, oracle.conv2d(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
+
+
+@pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
+def test_conv2d_configs(anr, name):
+    cfg = I.config_inputs(name)
+    s = cfg["shape"]
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d(dev(cfg["x"]), dev(cfg["w"]), y, s.stride, s.pad)
+    check_guard(buf)
+    assert_parity(y, oracle.conv2d(cfg["x"], cfg["w"], s.stride, s.pad), what=name)
+
+
+@pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
+def test_conv2d_configs_integer_exact(anr, name):
+    s = I.config_inputs(name)["shape"]
+    x, w = I.conv_inputs(s, 201, ints=True)
+    y = torch.empty((s.N, s.K, s.OH, s.OW), device="cuda")
+    anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+    assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), exact=True, what=name + " ints")
+
+
+def test_conv2d_delta_kernel_is_shift(anr):
+    C, H, W = 8, 12, 16
+    x = I.small_ints(np.random.Generator(np.random.PCG64(5)), (2, C, H, W))
+    for (r0, s0) in [(0, 0), (0, 2), (2, 1), (1, 1)]:
+        w = np.zeros((C, C, 3, 3), np.float32)
+        for c in range(C):
+            w[c, c, r0, s0] = 1.0
+        y = torch.empty((2, C, H, W), device="cuda")
+        anr.conv2d(dev(x), dev(w), y, (1, 1), (1, 1))
+        exp = np.zeros((2, C, H, W), np.float32)
+        for oh in range(H):
+            for ow in range(W):
+                ih, iw = oh + r0 - 1, ow + s0 - 1
+                if 0 <= ih < H and 0 <= iw < W:
+                    exp[:, :, oh, ow] = x[:, :, ih, iw]
+        assert np.array_equal(y.cpu().numpy(), exp)
+
+
+def test_conv2d_strided_views(anr):
+    # x is a window of a larger tensor and y is written into a larger tensor
+    s = I.ConvShape(2, 8, 12, 16, 16, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 202)
+    xw = torch.zeros((2, 10, 14, 24), device="cuda")
+    xw[:, 1:9, 1:13, 4:20] = dev(x)
+    yw = torch.full((2, 18, 13, 20), CANARY, device="cuda")
+    anr.conv2d(xw[:, 1:9, 1:13, 4:20], dev(w), yw[:, 1:17, 0:12, 4:20], s.stride, s.pad)
+    ref = oracle.conv2d(x, w, s.stride, s.pad)
+    assert_parity(yw[:, 1:17, 0:12, 4:20].contiguous(), ref, what="strided conv (aligned)")
+    assert float((yw == CANARY).sum()) == yw.numel() - ref.size
+    # an unaligned window (offset 1 in w) must give the same values through the generic kernel
+    xw2 = torch.zeros((2, 10, 14, 24), device="cuda")
+    xw2[:, 1:9, 1:13, 1:17] = dev(x)
+    y2 = torch.empty((2, 16, 12, 16), device="cuda")
+    anr.conv2d(xw2[:, 1:9, 1:13, 1:17], dev(w), y2, s.stride, s.pad)
+    assert_parity(y2, ref, what="strided conv (unaligned)")
+
+
+def test_conv2d_is_deterministic(anr):
+    s = I.ConvShape(2, 16, 28, 28, 64, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 203)
+    xd, wd = dev(x), dev(w)
+    y1 = torch.empty((2, 64, 28, 28), device="cuda")
+    y2 = torch.full((2, 64, 28, 28), float("nan"), device="cuda")
+    anr.conv2d(xd, wd, y1, s.stride, s.pad)
+    anr.conv2d(xd, wd, y2, s.stride, s.pad)
+    assert torch.equal(y1, y2)
+
+
+# ------------------------------------------------------------------ ConvLayer
+CONVLAYER_SHAPES = [
+    I.ConvShape(2, 8, 12, 12, 24, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(3, 16, 28, 28, 40, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 3, 16, 16, 8, 7, 7, (2, 2), (3, 3)),
+    I.ConvShape(2, 16, 10, 10, 12, 1, 1, (2, 2), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("shape", CONVLAYER_SHAPES, ids=str)
+def test_conv_bn_relu_small(anr, shape):
+    x, w = I.conv_inputs(shape, 300)
+    w = (w * 4).astype(np.float32)     # spread the pre-activation so that both ReLU branches are hit
+    gamma, beta, mean, var = I.bn_inputs(shape.K, 301)
+    buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y,
+                     shape.stride, shape.pad)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, shape.stride, shape.pad)
+    assert_parity(y, ref, what=str(shape))
+    got = y.cpu().numpy()
+    assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
+
+
+def test_conv_bn_relu_config(anr):
+    cfg = I.config_inputs("ConvLayer")
+    s = cfg["shape"]
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv_bn_relu(dev(cfg["x"]), dev(cfg["w"]), dev(cfg["gamma"]), dev(cfg["beta"]), dev(cfg["mean"]),
+                     dev(cfg["var"]), cfg["eps"], y, s.stride, s.pad)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu(cfg["x"], cfg["w"], cfg["gamma"], cfg["beta"], cfg["mean"], cfg["var"],
+                              cfg["eps"], s.stride, s.pad)
+    assert_parity(y, ref, what="ConvLayer")
+    assert (y >= 0).all()
+
+
+def test_conv_bn_relu_identity_bn_exact(anr):
+    # gamma=1, beta=0, mean=0, var+eps=1: the layer is exactly ReLU(conv) on integer inputs
+    s = I.ConvShape(2, 8, 12, 12, 16, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 302, ints=True)
+    K = s.K
+    one, zero = torch.ones(K, device="cuda"), torch.zeros(K, device="cuda")
+    var = torch.full((K,), 0.75, device="cuda")
+    y = torch.empty((2, K, 12, 12), device="cuda")
+    anr.conv_bn_relu(dev(x), dev(w), one, zero, zero, var, 0.25, y, s.stride, s.pad)
+    ref = np.maximum(oracle.conv2d(x, w, s.stride, s.pad), 0.0)
+    assert_parity(y, ref, exact=True, what="identity BN")
+
+
+# ------------------------------------------------------------------ depthwise
+DW_SHAPES = [
+    I.ConvShape(2, 5, 8, 8, 5, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(3, 20, 28, 28, 20, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 7, 13, 16, 7, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 3, 30, 112, 3, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 4, 7, 7, 4, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 6, 14, 14, 6, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 4, 17, 20, 4, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 3, 9, 10, 3, 5, 5, (1, 1), (2, 2)),
+    I.ConvShape(1, 2, 6, 260, 2, 3, 3, (1, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("shape", DW_SHAPES, ids=str)
+@pytest.mark.parametrize("ints", [False, True])
+def test_dwconv_small(anr, shape, ints):
+    x, w = I.dwconv_inputs(shape, 400, ints=ints)
+    buf, y = guarded((shape.N, shape.C, shape.OH, shape.OW))
+    anr.dwconv(dev(x), dev(w), y, shape.stride, shape.pad)
+    check_guard(buf)
+    assert_parity(y, oracle.dwconv(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
+
+
+def test_dwconv_config(anr):
+    cfg = I.config_inputs("DEP")
+    s = cfg["shape"]
+    buf, y = guarded((s.N, s.C, s.OH, s.OW))
+    anr.dwconv(dev(cfg["x"]), dev(cfg["w"]), y, s.stride, s.pad)
+    check_guard(buf)
+    assert_parity(y, oracle.dwconv(cfg["x"], cfg["w"], s.stride, s.pad), what="DEP")
+    x, w = I.dwconv_inputs(s, 401, ints=True)
+    anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+    assert_parity(y, oracle.dwconv(x, w, s.stride, s.pad), exact=True, what="DEP ints")
+
+
+def test_dwconv_strided_views(anr):
+    s = I.ConvShape(2, 6, 12, 16, 6, 3, 3, (1, 1), (1, 1))
+    x, w = I.dwconv_inputs(s, 402)
+    xw = torch.zeros((2, 8, 14, 24), device="cuda")
+    xw[:, 1:7, 1:13, 4:20] = dev(x)
+    yw = torch.full((2, 7, 13, 20), CANARY, device="cuda")
+    anr.dwconv(xw[:, 1:7, 1:13, 4:20], dev(w), yw[:, 1:7, 0:12, 4:20], s.stride, s.pad)
+    ref = oracle.dwconv(x, w, s.stride, s.pad)
+    assert_parity(yw[:, 1:7, 0:12, 4:20].contiguous(), ref, what="strided dwconv")
+    assert float((yw == CANARY).sum()) == yw.numel() - ref.size
+
+
+# ------------------------------------------------------------------ TBG / TBS
+TBG_SHAPES = [I.TbgShape(1, 1, 1, 1), I.TbgShape(2, 5, 3, 4), I.TbgShape(2, 70, 3, 20),
+              I.TbgShape(1, 128, 2, 64), I.TbgShape(2, 64, 3, 128), I.TbgShape(1, 130, 2, 33)]
+
+
+@pytest.mark.parametrize("shape", TBG_SHAPES, ids=str)
+@pytest.mark.parametrize("ints", [False, True])
+def test_tbg_small(anr, shape, ints):
+    q, k = I.tbg_inputs(shape, 500, ints=ints)
+    buf, out = guarded((shape.B, shape.H, shape.S, shape.S))
+    anr.tbg(dev(q), dev(k), out)
+    check_guard(buf)
+    assert_parity(out, oracle.tbg(q, k), exact=ints, what=str(shape))
+
+
+def test_tbg_config(anr):
+    cfg = I.config_inputs("TBG")
+    s = cfg["shape"]
+    buf, out = guarded((s.B, s.H, s.S, s.S))
+    anr.tbg(dev(cfg["q"]), dev(cfg["k"]), out)
+    check_guard(buf)
+    assert_parity(out, oracle.tbg(cfg["q"], cfg["k"]), what="TBG")
+
+
+def test_tbg_q_equals_k_is_symmetric(anr):
+    q, _ = I.tbg_inputs(I.TbgShape(2, 128, 3, 64), 501)
+    qd = dev(q)
+    out = torch.empty((2, 3, 128, 128), device="cuda")
+    anr.tbg(qd, qd, out)
+    o = out.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(o - o.transpose(0, 1, 3, 2)) / np.maximum(1.0, np.abs(o))) <= 1e-6
+    assert (np.einsum("bhii->bhi", o) >= 0).all()
+
+
+def test_tbg_one_hot_index_code(anr):
+    # which (b, h, i) met which j: catches a wrong transpose folded into the addressing
+    B, S, H, D = 2, 64, 3, 64
+    q = np.zeros((B, S, H, D), np.float32)
+    k = np.zeros((B, S, H, D), np.float32)
+    for b in range(B):
+        for s in range(S):
+            for h in range(H):
+                q[b, s, h, s % D] = 1.0
+                k[b, s, h, (s + 1) % D] = 1.0 + b + 10 * h
+    out = torch.empty((B, H, S, S), device="cuda")
+    anr.tbg(dev(q), dev(k), out)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.tbg(q, k))
+
+
+def test_tbg_strided_views(anr):
+    # q and k as the two halves of one fused [B,S,2,H,D] projection output
+    s = I.TbgShape(2, 40, 3, 16)
+    q, k = I.tbg_inputs(s, 502)
+    fused = torch.zeros((2, 40, 2, 3, 16), device="cuda")
+    fused[:, :, 0] = dev(q)
+    fused[:, :, 1] = dev(k)
+    out = torch.empty((2, 3, 40, 40), device="cuda")
+    anr.tbg(fused[:, :, 0], fused[:, :, 1], out)
+    assert_parity(out, oracle.tbg(q, k), what="strided tbg")
+
+
+@pytest.mark.parametrize("shape", [I.TbgShape(2, 5, 3, 4), I.TbgShape(1, 128, 2, 64),
+                                   I.TbgShape(1, 130, 2, 33), I.TbgShape(2, 64, 12, 128)], ids=str)
+def test_tbs_small(anr, shape):
+    q, k = I.tbg_inputs(shape, 503)
+    q = (q * 0.35).astype(np.float32)
+    buf, out = guarded((shape.B, shape.H, shape.S, shape.S))
+    anr.tbs(dev(q), dev(k), out)
+    check_guard(buf)
+    ref = oracle.tbs(q, k)
+    assert_parity(out, ref, what="tbs " + str(shape))
+    np.testing.assert_allclose(out.cpu().numpy().sum(-1), 1.0, atol=1e-5)
+
+
+def test_tbs_config_shape(anr):
+    cfg = I.config_inputs("TBG")
+    s = cfg["shape"]
+    out = torch.empty((s.B, s.H, s.S, s.S), device="cuda")
+    anr.tbs(dev(cfg["q"]), dev(cfg["k"]), out)
+    assert_parity(out, oracle.tbs(cfg["q"], cfg["k"]), what="TBS config")
+
+
+# ------------------------------------------------------------------ paper shape lists (Appendix C)
+def appendix_c(golden_dir):
+    import os
+    ops = {}
+    for line in open(os.path.join(golden_dir, "appendix_c_shapes.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            name, *vals = line.split()
+            ops.setdefault(name, []).append(tuple(int(v) for v in vals))
+    return ops
+
+
+def test_appendix_c_shapes_batch1(anr, golden_dir):
+    """Every GMM / C2D / DEP / ConvLayer / TBS shape of the paper's list at batch 1."""
+    ops = appendix_c(golden_dir)
+    for (n, m, k) in ops["GMM"]:
+        A, B = I.gemm_inputs(I.GemmShape(m, n, k), 600)
+        C = torch.empty((m, n), device="cuda")
+        anr.gemm(dev(A), dev(B), C)
+        assert_parity(C, oracle.gemm(A, B), what="GMM %s" % ((n, m, k),))
+    for (h, w_, ci, co, ks, st, pd) in ops["C2D"]:
+        s = I.ConvShape(1, ci, h, w_, co, ks, ks, (st, st), (pd, pd))
+        x, w = I.conv_inputs(s, 601)
+        y = torch.empty((1, co, s.OH, s.OW), device="cuda")
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+        assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), what="C2D " + str(s))
+    for (h, w_, c, ks, st, pd) in ops["DEP"]:
+        s = I.ConvShape(1, c, h, w_, c, ks, ks, (st, st), (pd, pd))
+        x, w = I.dwconv_inputs(s, 602)
+        y = torch.empty((1, c, s.OH, s.OW), device="cuda")
+        anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+        assert_parity(y, oracle.dwconv(x, w, s.stride, s.pad), what="DEP " + str(s))
+    for (h, w_, ci, co, ks, st, pd) in ops["ConvLayer"]:
+        s = I.ConvShape(1, ci, h, w_, co, ks, ks, (st, st), (pd, pd))
+        x, w = I.conv_inputs(s, 603)
+        gamma, beta, mean, var = I.bn_inputs(co, 604)
+        y = torch.empty((1, co, s.OH, s.OW), device="cuda")
+        anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y,
+                         s.stride, s.pad)
+        ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+        assert_parity(y, ref, what="ConvLayer " + str(s))
+    for (S, H, D) in ops["TBS"]:
+        s = I.TbgShape(1, S, H, D)
+        q, k = I.tbg_inputs(s, 605)
+        q = (q * 0.35).astype(np.float32)
+        out = torch.empty((1, H, S, S), device="cuda")
+        anr.tbg(dev(q), dev(k), out)
+        assert_parity(out, oracle.tbg(q, k), what="TBG " + str(s))
+        anr.tbs(dev(q), dev(k), out)
+        assert_parity(out, oracle.tbs(q, k), what="TBS " + str(s))
