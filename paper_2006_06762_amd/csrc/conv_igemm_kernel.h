@@ -1,0 +1,481 @@
+// C2D and the ConvLayer subgraph (Sec. 7.1, Sec. 7.2 and Appendix C of
+// arXiv 2006.06762) as an implicit GEMM on the fp32 MFMA units of gfx950.
+//
+// GEMM view: rows m = flattened output pixels (n, oh, ow), columns = output
+// channels, reduction = (c, r, s).  A work-group owns BM consecutive pixels x BN
+// channels and walks the input channels in chunks of CK.
+//
+// What is staged in LDS is NOT an im2col matrix but the raw input patch the
+// tile needs: for every channel of the chunk, the input rows from the first to
+// the last one any of the tile's pixels touches, each row with its left/right
+// zero padding.  Rows are addressed in "virtual image" coordinates (all images
+// stacked, each with its zero rows above and below), so a tile may straddle
+// image boundaries without special cases.  Every tap (r, s) then reads the
+// same patch at a different constant offset, so an input element crosses
+// HBM/L2 -> LDS once per tile instead of R*S times.  Rows and columns that are
+// padding are zeroed once, before the first chunk, and never written again.
+//
+// MFMA: v_mfma_f32_32x32x2_f32 (measured on MI355X: it sustains 99 % of the
+// 157.3 TFLOP/s fp32 matrix peak from one wave per SIMD, the 16x16x4 form only
+// 78-85 %).  Lane l feeds pixel (l%32) of a 32-pixel block for the A operand
+// and channel (l%32) of a 32-channel block for B; its half h = l/32 picks which
+// of the two k values of the instruction it supplies.  A half-wave walks "its"
+// CPH channels of the chunk, tap by tap, so the A address of a lane is one
+// per-lane base plus an offset that is uniform over the wave, and the B
+// (weight) values of a lane are consecutive floats of the natural OIHW order:
+// weights are copied to LDS unpermuted.
+//
+// Waves: WAVES_M x WAVES_N wave tiles of (32*WM_BLK) x (32*WN_BLK), times
+// KSPLIT waves per tile that split the k-steps of every chunk among them (the
+// tile shapes that divide the benchmark problems evenly over 256 CUs have an
+// odd number of 32-pixel blocks, so the waves of a work-group share a tile
+// along k instead of cutting it).  After the last chunk the partial
+// accumulators are reduce-scattered through LDS: every 32x32 block has an owner
+// wave that sums the others' partials and runs the epilogue for that block, so
+// the reduction takes one barrier and the stores are spread over all waves.
+//
+// Inside a chunk the operands of step t+1 are read from LDS before the MFMAs
+// of step t are issued (register double buffering).  Staging of the next chunk
+// is woven into the MFMA stream one instruction at a time: an MFMA occupies the
+// matrix pipe for 64 cycles but the wave only 4 to issue it, so one global load
+// goes out behind each of the first MFMAs of a chunk and one LDS store behind
+// each of the last ones, and neither costs matrix time.  Loads and stores are
+// branch-free (spare staging slots duplicate a real unit, padding rows store
+// zeros): a load inside a divergent branch makes the compiler drain all
+// outstanding loads first, which serialises a chunk's memory latency.
+// One barrier per chunk.
+//
+// The batch-norm scale/shift and ReLU of ConvLayer run on the accumulators in
+// the epilogue (Table 1, rule 4: fuse element-wise consumers into the tiled
+// node); results are written straight from registers, 16 bytes per lane.
+#pragma once
+#include <type_traits>
+
+#include "anr_device.h"
+#include "conv_internal.h"
+
+namespace anr {
+namespace igemm {
+
+// floor(n / d) for 0 <= n < 2^31 as one multiply-high and one shift (Granlund-Montgomery
+// round-up method: mul = ceil(2^(31+l) / d), l = ceil(log2 d), quotient = (n*mul) >> (31+l)).
+struct FastDiv {
+    uint32_t mul, shr;
+    __device__ __forceinline__ int div(int n) const
+    {
+        return mul ? (int)(__umulhi((uint32_t)n, mul) >> shr) : n;
+    }
+};
+
+inline FastDiv make_fastdiv(int d)
+{
+    FastDiv f{0u, 0u};
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1ll << l) < d) ++l;
+    f.mul = (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)d - 1) / (uint64_t)d);
+    f.shr = (uint32_t)(l - 1);
+    return f;
+}
+
+struct Geom {
+    int Mtot;       // N*OH*OW
+    int HV;         // virtual image height: (OH-1)*stride_h + R
+    int VR;         // virtual rows staged per tile (max over tiles)
+    int RSL;        // LDS row stride, floats
+    int P;          // LDS channel-plane stride, floats
+    int XC;         // LDS column of input column 0 (multiple of 4)
+    int W4;         // W / 4
+    int n_units;    // CK * VR * W4 16-byte staging units per chunk
+    int vec_store;  // 4 consecutive pixels of a lane are 16 contiguous, aligned bytes of y
+    int ohow;       // OH*OW
+    FastDiv d_ow, d_oh, d_hv, d_w4, d_perc, d_ohow, d_units;   // divisors OW, OH, HV, W4, VR*W4, OH*OW, n_units
+#ifdef ANR_IGEMM_TRACE
+    long long* trace;   // experiment harness only: per-work-group phase timestamps
+#endif
+};
+
+#ifdef ANR_IGEMM_TRACE
+#define ANR_TRACE(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
+#define ANR_TRACE_END(slot) do { __builtin_amdgcn_s_waitcnt(0); ANR_TRACE(slot); } while (0)
+#define ANR_TRACE_CLK(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = clock64(); } while (0)
+#else
+#define ANR_TRACE_CLK(slot) do { } while (0)
+#define ANR_TRACE(slot) do { } while (0)
+#define ANR_TRACE_END(slot) do { } while (0)
+#endif
+
+constexpr int kMaxUnits = 8;
+
+template <int WM_BLK, int WN_BLK, int WAVES_M, int WAVES_N, int KSPLIT, int R_, int S_, int CPH, int XU,
+          int RSL_T, int P_T>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT)
+void conv_igemm_kernel(const ConvArgs p, const Geom g)
+{
+    constexpr int NT = 64 * WAVES_M * WAVES_N * KSPLIT;
+    constexpr int BM = 32 * WM_BLK * WAVES_M, BN = 32 * WN_BLK * WAVES_N;
+    constexpr int RS9 = R_ * S_;
+    constexpr int CK = 2 * CPH;           // channels per chunk
+    constexpr int KC = CK * RS9;          // reduction length per chunk
+    constexpr int WS = KC + 2;            // LDS stride of one output channel's weights
+    constexpr int STEPS = CPH * RS9;      // MFMA k-steps per chunk (all waves of a tile together)
+    constexpr int SPW = STEPS / KSPLIT;   // k-steps per chunk of one wave
+    constexpr int WQ = KC / 4;
+    constexpr int WU = (BN * WQ + NT - 1) / NT;
+    constexpr int NBLK = WM_BLK * WN_BLK; // MFMAs per k-step of one wave
+    constexpr int SLOTS = SPW * NBLK;     // MFMAs per chunk of one wave = issue slots for staging
+    constexpr int NSIDE = XU + WU;        // staging units per thread and chunk
+    constexpr int STORE0 = SLOTS - NSIDE; // the last NSIDE slots carry the LDS stores
+    static_assert(KC % 4 == 0, "chunk must be a whole number of float4");
+    static_assert(CPH % KSPLIT == 0, "waves split a half-wave's channels evenly");
+    static_assert(2 * NSIDE <= SLOTS, "not enough MFMAs in a chunk to hide the staging behind");
+
+    // LDS geometry: compile-time for the instantiations made for one problem shape (every LDS
+    // address in the main loop is then a per-lane register plus an instruction immediate, and
+    // the loop holds no vector ALU instruction at all: on this hardware each VALU or VMEM
+    // instruction between two MFMAs delays the second by 5-13 cycles, LDS and scalar ones do not)
+    const int RSL = RSL_T ? RSL_T : g.RSL;
+    const int P = P_T ? P_T : g.P;
+    const int patch_sz = CK * P;                     // floats per patch buffer
+    constexpr int WTS_SZ = BN * WS;                  // floats per weight buffer
+
+    ANR_TRACE(0);
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    // layout: patch[2][patch_sz], then wts[2][WTS_SZ]
+    char* const lds = reinterpret_cast<char*>(smem);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int tile_wave = wave % (WAVES_M * WAVES_N), ks = wave / (WAVES_M * WAVES_N);
+    const int wave_m = tile_wave / WAVES_N, wave_n = tile_wave % WAVES_N;
+    const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+
+    const int g0 = g.d_ow.div(m0);
+    const int n_first = g.d_oh.div(g0);
+    const int v0 = n_first * g.HV + (g0 - n_first * p.OH) * p.stride_h;
+
+    // ---- staging descriptors: which 16 bytes of x go where in the patch (fixed over chunks).
+    //      Every slot of every thread loads something, so that the main loop has no branch
+    //      around a load: slots past the end of the patch duplicate an earlier unit (same data
+    //      to the same place), units whose row is padding load offset 0 and skip the store
+    //      (their rows were zeroed before the first chunk).  Offsets are in bytes, relative to
+    //      the first channel of a chunk.
+    uint32_t xoff[XU], xlds[XU];
+    bool xvalid[XU];
+#pragma unroll
+    for (int i = 0; i < XU; ++i) {
+        int u = tid + i * NT;
+        u -= g.d_units.div(u) * g.n_units;
+        const int ci = g.d_perc.div(u), rem = u - ci * (g.VR * g.W4);
+        const int vr = g.d_w4.div(rem), j4 = rem - vr * g.W4;
+        const int v = v0 + vr;
+        const int n = g.d_hv.div(v), ih = v - n * g.HV - p.pad_h;
+        xvalid[i] = n < p.N && ih >= 0 && ih < p.H;
+        xoff[i] = xvalid[i] ? 4u * (uint32_t)(n * p.xs[0] + ci * p.xs[1] + ih * p.xs[2] + 4 * j4) : 0u;
+        xlds[i] = 4u * (uint32_t)(ci * P + vr * RSL + g.XC + 4 * j4);
+    }
+    // weight staging: unit u is 16 bytes of output channel co0 + u / WQ; slots past the tile
+    // duplicate earlier units, channels past K re-read the last valid channel (their products
+    // land in accumulator columns that are never stored)
+    uint32_t woff[WU], wlds[WU];
+#pragma unroll
+    for (int i = 0; i < WU; ++i) {
+        const int u = (tid + i * NT) % (BN * WQ);
+        const int co = u / WQ, kq = u - co * WQ;
+        const int gco = co0 + co < p.K ? co0 + co : p.K - 1;
+        woff[i] = 4u * (uint32_t)(gco * (p.C * RS9) + 4 * kq);
+        wlds[i] = 4u * (uint32_t)(2 * patch_sz + co * WS + 4 * kq);
+    }
+
+    // ---- per-lane operand addresses in LDS, bytes (the wave's share of the k-steps is folded in)
+    uint32_t abase[WM_BLK];
+#pragma unroll
+    for (int mb = 0; mb < WM_BLK; ++mb) {
+        int m = m0 + (wave_m * WM_BLK + mb) * 32 + r32;
+        m = m < g.Mtot ? m : g.Mtot - 1;
+        const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+        const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+        const int vrel = n * g.HV + oh * p.stride_h - v0;
+        abase[mb] = 4u * (uint32_t)((h * CPH + ks * (CPH / KSPLIT)) * P + vrel * RSL + (g.XC - p.pad_w) +
+                                    ow * p.stride_w);
+    }
+    uint32_t bbase[WN_BLK];
+#pragma unroll
+    for (int nb = 0; nb < WN_BLK; ++nb)
+        bbase[nb] = 4u * (uint32_t)(2 * patch_sz + ((wave_n * WN_BLK + nb) * 32 + r32) * WS + h * CPH * RS9 +
+                                    ks * SPW);
+
+    f32x16 acc[WM_BLK][WN_BLK];
+#pragma unroll
+    for (int mb = 0; mb < WM_BLK; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < WN_BLK; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    f32x4 rx[XU], rw[WU];
+    const int nchunks = p.C / CK;
+
+    // staging unit j: global -> registers (uniform 64-bit base + 32-bit per-lane byte offset)
+    auto side_load = [&](int j, const char* __restrict__ xb, const char* __restrict__ wb) {
+        if (j < XU) rx[j] = *reinterpret_cast<const f32x4*>(xb + xoff[j]);
+        else rw[j - XU] = *reinterpret_cast<const f32x4*>(wb + woff[j - XU]);
+    };
+    // staging unit j: registers -> LDS, xbuf_b / wbuf_b = byte offset of the target buffer
+    auto side_store = [&](int j, int xbuf_b, int wbuf_b) {
+        if (j < XU) {
+            if (xvalid[j]) *reinterpret_cast<f32x4*>(lds + xlds[j] + xbuf_b) = rx[j];
+        } else {
+            const f32x4 v = rw[j - XU];
+            f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+            f32x2* dst = reinterpret_cast<f32x2*>(lds + wlds[j - XU] + wbuf_b);
+            dst[0] = lo;
+            dst[1] = hi;
+        }
+    };
+
+    ANR_TRACE(1);
+#pragma unroll
+    for (int j = 0; j < NSIDE; ++j)
+        side_load(j, reinterpret_cast<const char*>(p.x), reinterpret_cast<const char*>(p.w));
+    for (int idx = tid; idx < (2 * patch_sz) / 4; idx += NT)
+        reinterpret_cast<f32x4*>(smem)[idx] = zero4();
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NSIDE; ++j) side_store(j, 0, 0);
+    __syncthreads();
+    ANR_TRACE(2);
+    ANR_TRACE_CLK(6);
+
+    // One chunk: MFMAs on LDS buffer `buf`, staging of chunk cc+1 into the other buffer.
+    auto chunk = [&](int cc, auto buf_c) {
+        constexpr int buf = decltype(buf_c)::value;
+        // the chunk after the last one is the last one again: loaded and stored, never read
+        const int cn = cc + 1 < nchunks ? cc + 1 : cc;
+        const char* __restrict__ xb = reinterpret_cast<const char*>(p.x + (int64_t)cn * CK * p.xs[1]);
+        const char* __restrict__ wb = reinterpret_cast<const char*>(p.w + (int64_t)cn * KC);
+        const int rd_a = 4 * buf * patch_sz, rd_b = 4 * buf * WTS_SZ;
+        const int st_a = 4 * (buf ^ 1) * patch_sz, st_b = 4 * (buf ^ 1) * WTS_SZ;
+
+        float a_cur[WM_BLK], b_cur[WN_BLK], a_nxt[WM_BLK], b_nxt[WN_BLK];
+        auto read_step = [&](int t, float* a, float* b) {
+            const int cl = t / RS9, tap = t % RS9;
+            const int offA = 4 * (cl * P + (tap / S_) * RSL + (tap % S_)) + rd_a;
+#pragma unroll
+            for (int mb = 0; mb < WM_BLK; ++mb) a[mb] = *reinterpret_cast<const float*>(lds + abase[mb] + offA);
+#pragma unroll
+            for (int nb = 0; nb < WN_BLK; ++nb)
+                b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + rd_b);
+        };
+        read_step(0, a_cur, b_cur);
+#pragma unroll
+        for (int t = 0; t < SPW; ++t) {
+            // reads of step t+1 are issued before the MFMAs of step t: their latency hides
+            // behind those MFMAs instead of stalling the next ones
+            if (t + 1 < SPW) read_step(t + 1, a_nxt, b_nxt);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mb = 0; mb < WM_BLK; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < WN_BLK; ++nb) {
+                    acc[mb][nb] = mfma32(a_cur[mb], b_cur[nb], acc[mb][nb]);
+                    const int slot = (t * WM_BLK + mb) * WN_BLK + nb;
+                    if (slot < NSIDE) side_load(slot, xb, wb);
+                    if (slot >= STORE0) side_store(slot - STORE0, st_a, st_b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+            for (int mb = 0; mb < WM_BLK; ++mb) a_cur[mb] = a_nxt[mb];
+#pragma unroll
+            for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
+        }
+        __syncthreads();
+    };
+    for (int cc = 0; cc < nchunks; cc += 2) {
+        chunk(cc, std::integral_constant<int, 0>{});
+        if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
+    }
+
+    ANR_TRACE(3);
+    ANR_TRACE_CLK(7);
+    // ---- reduce-scatter of the k-split partial accumulators: block b belongs to wave ks == b % KSPLIT
+    //      of its tile; the others leave their partials in LDS (the staging buffers are free now)
+    if (KSPLIT > 1) {
+        f32x4* red = reinterpret_cast<f32x4*>(smem);
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const int owner = b % KSPLIT;
+            if (ks != owner) {
+                const int src = (ks - owner - 1 + KSPLIT) % KSPLIT;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const f32x16& c = acc[b / WN_BLK][b % WN_BLK];
+                    f32x4 t = {c[4 * v], c[4 * v + 1], c[4 * v + 2], c[4 * v + 3]};
+                    red[((((tile_wave * NBLK + b) * (KSPLIT - 1)) + src) * 4 + v) * 64 + lane] = t;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            if (ks == b % KSPLIT) {
+#pragma unroll
+                for (int src = 0; src < KSPLIT - 1; ++src)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const f32x4 t = red[((((tile_wave * NBLK + b) * (KSPLIT - 1)) + src) * 4 + v) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[b / WN_BLK][b % WN_BLK][4 * v + e] += t[e];
+                    }
+            }
+        }
+    }
+    ANR_TRACE(4);
+
+    // ---- epilogue, per owned block: accumulator register r of lane (h, r32) is pixel
+    //      8*(r/4) + 4*h + r%4, channel r32 of the 32x32 block: four consecutive pixels per quad
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int mb = b / WN_BLK, nb = b % WN_BLK;
+        if (ks != b % KSPLIT) continue;
+        const int co = co0 + (wave_n * WN_BLK + nb) * 32 + r32;
+        if (co >= p.K) continue;
+        float scale = 1.f, shift = 0.f;
+        if (p.gamma) {
+            scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
+            shift = p.beta[co] - p.mean[co] * scale;
+        }
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int mq = m0 + (wave_m * WM_BLK + mb) * 32 + 8 * v4 + 4 * h;
+            f32x4 v = {acc[mb][nb][4 * v4], acc[mb][nb][4 * v4 + 1], acc[mb][nb][4 * v4 + 2],
+                       acc[mb][nb][4 * v4 + 3]};
+            if (p.gamma) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = fmaxf(fmaf(v[r], scale, shift), 0.f);
+            }
+            if (g.vec_store) {
+                if (mq < g.Mtot) {
+                    const int n = g.d_ohow.div(mq), pix = mq - n * g.ohow;
+                    stg4(p.y + n * p.ys[0] + co * p.ys[1] + pix, v);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = mq + r;
+                    if (m < g.Mtot) {
+                        const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+                        const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+                        p.y[n * p.ys[0] + co * p.ys[1] + oh * p.ys[2] + ow] = v[r];
+                    }
+                }
+            }
+        }
+    }
+    ANR_TRACE_END(5);
+}
+
+// Largest number of virtual rows any M-tile of BM pixels needs.
+inline int max_virtual_rows(const ConvArgs& a, int BM, int HV)
+{
+    const int64_t Mtot = (int64_t)a.N * a.OH * a.OW;
+    int vr = 0;
+    for (int64_t m0 = 0; m0 < Mtot; m0 += BM) {
+        const int64_t m1 = (m0 + BM < Mtot ? m0 + BM : Mtot) - 1;
+        const int64_t g0 = m0 / a.OW, g1 = m1 / a.OW;
+        const int64_t va = (g0 / a.OH) * HV + (g0 % a.OH) * a.stride_h;
+        const int64_t vb = (g1 / a.OH) * HV + (g1 % a.OH) * a.stride_h;
+        const int need = (int)(vb - va) + a.R;
+        if (need > vr) vr = need;
+    }
+    return vr;
+}
+
+template <int WM_BLK, int WN_BLK, int WAVES_M, int WAVES_N, int KSPLIT, int R_, int S_, int CPH>
+struct Variant {
+    static constexpr int NT = 64 * WAVES_M * WAVES_N * KSPLIT;
+    static constexpr int BM = 32 * WM_BLK * WAVES_M, BN = 32 * WN_BLK * WAVES_N;
+    static constexpr int CK = 2 * CPH;
+    static constexpr int WS = CK * R_ * S_ + 2;
+
+    // Fills the geometry; false if this variant cannot run the problem.
+    static bool plan(const ConvArgs& a, Geom* g, size_t* lds_bytes)
+    {
+        if (a.R != R_ || a.S != S_ || a.C % CK != 0) return false;
+        g->Mtot = a.N * a.OH * a.OW;
+        g->ohow = a.OH * a.OW;
+        g->HV = (a.OH - 1) * a.stride_h + a.R;
+        g->VR = max_virtual_rows(a, BM, g->HV);
+        g->XC = (a.pad_w + 3) / 4 * 4;
+        const int wv = (a.OW - 1) * a.stride_w + a.S;           // virtual row width
+        const int need_cols = g->XC - a.pad_w + (wv > a.W + a.pad_w ? wv : a.W + a.pad_w);
+        g->RSL = (need_cols + 3) / 4 * 4;
+        g->P = g->VR * g->RSL;
+        g->W4 = a.W / 4;
+        g->n_units = CK * g->VR * g->W4;
+        if (g->n_units > kMaxUnits * NT) return false;
+        // virtual row numbers must stay below 2^31 for the fast division
+        if ((int64_t)a.N * g->HV + g->VR >= ((int64_t)1 << 31)) return false;
+        g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) &&
+                       (a.ys[1] % 4 == 0) && is_aligned16(a.y);
+        g->d_ow = make_fastdiv(a.OW);
+        g->d_oh = make_fastdiv(a.OH);
+        g->d_hv = make_fastdiv(g->HV);
+        g->d_w4 = make_fastdiv(g->W4);
+        g->d_perc = make_fastdiv(g->VR * g->W4);
+        g->d_ohow = make_fastdiv(g->ohow);
+        g->d_units = make_fastdiv(g->n_units);
+        size_t floats = 2 * ((size_t)CK * g->P + (size_t)BN * WS);
+        // the k-split reduction reuses the staging memory
+        const size_t red = (size_t)(KSPLIT - 1) * WAVES_M * WAVES_N * WM_BLK * WN_BLK * 64 * 16;
+        if (red > floats) floats = red;
+        *lds_bytes = sizeof(float) * floats;
+        return *lds_bytes <= 160 * 1024;
+    }
+
+    template <int XU, int RSL_T, int P_T>
+    static hipError_t launch_inst(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    {
+        auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T>;
+        if (lds_bytes > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+        }
+        dim3 grid((g.Mtot + BM - 1) / BM, (a.K + BN - 1) / BN);
+        return launch_kernel(kern, grid, dim3(NT), lds_bytes, stream, a, g);
+    }
+
+    static int units_per_thread(const Geom& g) { return (g.n_units + NT - 1) / NT; }
+
+    // Instantiation with the LDS geometry (row stride, plane stride) and the number of staging
+    // units per thread fixed at compile time; the caller has checked that g matches.
+    template <int XU, int RSL_T, int P_T>
+    static hipError_t launch_fixed(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    {
+        return launch_inst<XU, RSL_T, P_T>(a, g, lds_bytes, stream);
+    }
+
+    // Any geometry: LDS strides are run-time values (address arithmetic stays in the loop).
+    static hipError_t launch(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    {
+        const int per_thread = units_per_thread(g);
+        if (per_thread <= 2) return launch_inst<2, 0, 0>(a, g, lds_bytes, stream);
+        if (per_thread <= 4) return launch_inst<4, 0, 0>(a, g, lds_bytes, stream);
+        if (per_thread <= 6) return launch_inst<6, 0, 0>(a, g, lds_bytes, stream);
+        return launch_inst<kMaxUnits, 0, 0>(a, g, lds_bytes, stream);
+    }
+
+    // Relative cost: rounds of work-groups over the 256 CUs times the tile volume.
+    static double cost(const ConvArgs& a)
+    {
+        const int64_t Mtot = (int64_t)a.N * a.OH * a.OW;
+        const int64_t wgs = ((Mtot + BM - 1) / BM) * ((a.K + BN - 1) / BN);
+        const int64_t rounds = (wgs + 255) / 256;
+        return (double)rounds * BM * BN;
+    }
+};
+
+}  // namespace igemm
+}  // namespace anr
