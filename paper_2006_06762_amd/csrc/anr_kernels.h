@@ -39,6 +39,11 @@ struct GemmArgs {
     bool softmax_rows;   // TBS: softmax over each output row (requires N <= 1024)
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+// The TBS batch matmul (a.b_is_nk set, batch = B*H, batch_inner = H), optionally followed by the
+// row softmax; picks the dedicated tile kernel when the operands allow it.
+hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream);
+// In-place softmax over every row of the a.batch output matrices of `a` (a.N <= 1024).
+hipError_t launch_softmax_rows(const GemmArgs& a, hipStream_t stream);
 
 struct ConvArgs {
     const float* x;

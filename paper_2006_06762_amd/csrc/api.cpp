@@ -155,7 +155,7 @@ anr_status run_tbg(const anr_tbg_desc* d, const float* q, const float* k, float*
     a.sCo = g.os[0]; a.sCi = g.os[1];
     a.b_is_nk = true;
     a.softmax_rows = softmax;
-    return launch_status(anr::launch_gemm(a, static_cast<hipStream_t>(hip_stream)));
+    return launch_status(anr::launch_tbg(a, static_cast<hipStream_t>(hip_stream)));
 }
 
 }  // namespace

@@ -286,12 +286,15 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
     }
     if (err != hipSuccess) return err;
 
-    if (a.softmax_rows) {
-        const int64_t rows = (int64_t)a.batch * a.M;
-        err = launch_kernel(softmax_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
-                            a.C, rows, a.N, a.M, a.batch_inner, a.sCo, a.sCi, a.ldc);
-    }
+    if (a.softmax_rows) err = launch_softmax_rows(a, stream);
     return err;
+}
+
+hipError_t launch_softmax_rows(const GemmArgs& a, hipStream_t stream)
+{
+    const int64_t rows = (int64_t)a.batch * a.M;
+    return launch_kernel(softmax_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
+                         a.C, rows, a.N, a.M, a.batch_inner, a.sCo, a.sCi, a.ldc);
 }
 
 }  // namespace anr
