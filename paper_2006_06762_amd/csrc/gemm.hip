@@ -56,15 +56,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs p)
             const int row = u / KQ, kq = u % KQ;
             const int gr = row0 + row, gk = kt * BK + kq * 4;
             f32x4 v = zero4();
-            if (gr < rows_total) {
+            if (VEC) {
+                // branch-free: out-of-range units re-read a valid address and are zeroed by a
+                // select (a load under a divergent branch would serialise the loads of a tile)
+                const bool in = gr < rows_total && gk < K;
+                const float* src = base + (int64_t)(in ? gr : 0) * ld + (in ? gk : 0);
+                const f32x4 t = ldg4(src);
+                v = in ? t : v;
+            } else if (gr < rows_total) {
                 const float* src = base + (int64_t)gr * ld + gk;
-                if (VEC) {
-                    if (gk < K) v = ldg4(src);
-                } else {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (gk + c < K) v[c] = src[c];
-                }
+                for (int c = 0; c < 4; ++c)
+                    if (gk + c < K) v[c] = src[c];
             }
             reg[i] = v;
         }
@@ -85,15 +88,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs p)
             const int k = u / NQ, nq = u % NQ;
             const int gk = kt * BK + k, gn = bn0 + nq * 4;
             f32x4 v = zero4();
-            if (gk < K) {
+            if (VEC) {
+                const bool in = gk < K && gn < N;
+                const float* src = B + (int64_t)(in ? gk : 0) * p.ldb + (in ? gn : 0);
+                const f32x4 t = ldg4(src);
+                v = in ? t : v;
+            } else if (gk < K) {
                 const float* src = B + (int64_t)gk * p.ldb + gn;
-                if (VEC) {
-                    if (gn < N) v = ldg4(src);
-                } else {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (gn + c < N) v[c] = src[c];
-                }
+                for (int c = 0; c < 4; ++c)
+                    if (gn + c < N) v[c] = src[c];
             }
             rb[i] = v;
         }
@@ -250,6 +254,137 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* out, int64_t r
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Small problems (few output tiles, long K), e.g. the 512^3 GMM of the benchmark: 268 MFLOP
+// are 64 MFMAs per SIMD if and only if all 1024 SIMDs take part, so a work-group owns one
+// 32 x 32 tile of C and its four waves split K.  The waves share no operand; each stages its
+// own slices of A (32 rows x K/4) and B (K/4 x 32) through a private region of LDS purely to
+// turn fully coalesced 16-byte global loads (whole 128-byte lines, eight per instruction)
+// into the per-lane operand order of the MFMA: issuing the operand loads straight from
+// global memory costs 2.8 us of address-unit time for this shape, the staged form a third
+// of that.  All loads of a wave are in flight before its first MFMA.  The four partial
+// tiles meet in LDS once; every wave then sums and stores 8 rows.  Work-group ids are
+// mapped to tiles so that the 32 work-groups that land on one XCD (ids are dealt round-robin
+// over the 8 XCDs) form a compact block of C and share their panels of A and B in that
+// XCD's L2.
+#ifdef ANR_GEMM_TRACE
+__device__ long long* anr_gemm_trace = nullptr;
+#define GT(slot) do { if (threadIdx.x == 0 && anr_gemm_trace) anr_gemm_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#define GT_END(slot) do { __builtin_amdgcn_s_waitcnt(0); GT(slot); } while (0)
+#else
+#define GT(slot) do { } while (0)
+#define GT_END(slot) do { } while (0)
+#endif
+
+constexpr int kKsLd = 36;                       // LDS row stride (floats) of a 32-wide stage
+constexpr int kKsStage = 2 * 32 * kKsLd;        // floats per stage: A block then B block
+
+template <int NST>
+__global__ __launch_bounds__(256) void gemm_tile32_ksplit_kernel(const GemmArgs p, int tiles_m, int tiles_n,
+                                                                 int xcd_map)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // [4 waves][NST][kKsStage]
+    GT(0);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+
+    int tm, tn;
+    const int w = blockIdx.x;
+    if (xcd_map) {
+        const int xcd = w & 7, slot = w >> 3;
+        const int rows_per = tiles_m / 4, cols_per = tiles_n / 2;
+        tm = (xcd >> 1) * rows_per + slot / cols_per;
+        tn = (xcd & 1) * cols_per + slot % cols_per;
+    } else {
+        tm = w / tiles_n;
+        tn = w % tiles_n;
+    }
+    const float* __restrict__ A = p.A + blockIdx.z * p.sAo;
+    const float* __restrict__ B = p.B + blockIdx.z * p.sBo;
+    float* __restrict__ C = p.C + blockIdx.z * p.sCo;
+
+    // staging unit of a lane: row lane/8 (+8 per t), 16 bytes at column 4*(lane%8)
+    const int srow = lane >> 3, sq = (lane & 7) * 4;
+    const int kbase = wave * (NST * 32);
+    const float* __restrict__ ap = A + (int64_t)(tm * 32 + srow) * p.lda + kbase + sq;
+    const float* __restrict__ bp = B + (int64_t)(kbase + srow) * p.ldb + tn * 32 + sq;
+    float* const wl = lds + wave * (NST * kKsStage);
+
+    f32x4 ra[NST][4], rb[NST][4];
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ra[s][t] = ldg4(ap + (int64_t)(8 * t) * p.lda + s * 32);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) rb[s][t] = ldg4(bp + (int64_t)(s * 32 + 8 * t) * p.ldb);
+    }
+    // keep every load above the first use (the scheduler would otherwise sink each load to
+    // its use to save registers, and the wave would see one memory latency per stage)
+    __builtin_amdgcn_sched_barrier(0);
+    GT(1);
+
+    f32x16 acc, acc2;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        float* st = wl + s * kKsStage;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            *reinterpret_cast<f32x4*>(&st[(srow + 8 * t) * kKsLd + sq]) = ra[s][t];
+            *reinterpret_cast<f32x4*>(&st[32 * kKsLd + (srow + 8 * t) * kKsLd + sq]) = rb[s][t];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const f32x4 av = *reinterpret_cast<const f32x4*>(&st[r32 * kKsLd + kk * 8 + 4 * h]);
+            float bv[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bv[e] = st[32 * kKsLd + (kk * 8 + 4 * h + e) * kKsLd + r32];
+            acc = mfma32(av[0], bv[0], acc);
+            acc2 = mfma32(av[1], bv[1], acc2);
+            acc = mfma32(av[2], bv[2], acc);
+            acc2 = mfma32(av[3], bv[3], acc2);
+        }
+    }
+
+    GT(2);
+    __syncthreads();            // every wave is done with its staging region: reuse it
+    float* red = lds;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r] + acc2[r];
+    __syncthreads();
+    GT(3);
+    // wave w finishes accumulator registers 4w .. 4w+3: rows 8w + 4h + q of the tile
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = wave * 4 + q;
+        const float v = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
+                        red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
+        C[(int64_t)(tm * 32 + 8 * wave + 4 * h + q) * p.ldc + tn * 32 + r32] = v;
+    }
+    GT_END(4);
+}
+
+template <int NST>
+hipError_t launch_ksplit(const GemmArgs& a, hipStream_t stream)
+{
+    const int tiles_m = a.M / 32, tiles_n = a.N / 32;
+    const size_t lds_bytes = sizeof(float) * 4 * NST * kKsStage;
+    auto kern = gemm_tile32_ksplit_kernel<NST>;
+    if (lds_bytes > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    const int xcd_map = (tiles_m % 4 == 0) && (tiles_n % 2 == 0);
+    return launch_kernel(kern, dim3(tiles_m * tiles_n, 1, a.batch), dim3(256), lds_bytes, stream, a, tiles_m,
+                         tiles_n, xcd_map);
+}
+
 template <int BM, int BN, int BK, bool NT, bool VEC>
 hipError_t launch_variant(const GemmArgs& a, hipStream_t stream)
 {
@@ -271,6 +406,15 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
 
     const int64_t tiles128 = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
     const bool big = tiles128 >= 192;   // enough 128x128 tiles to occupy most of the 256 CUs
+
+    // few tiles and a long reduction: one 32x32 tile per work-group, K split over its waves
+    const int64_t tiles32 = (int64_t)(a.M / 32) * (a.N / 32) * a.batch;
+    if (!a.b_is_nk && !a.softmax_rows && (a.M % 32 == 0) && (a.N % 32 == 0) && tiles32 <= 1024 &&
+        a.batch_inner == 1 && aligned16(a.A) && aligned16(a.B) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) &&
+        (a.sAo % 4 == 0) && (a.sBo % 4 == 0) && a.batch <= 65535) {
+        if (a.K == 256) return launch_ksplit<2>(a, stream);
+        if (a.K == 512) return launch_ksplit<4>(a, stream);
+    }
 
     hipError_t err;
     if (a.b_is_nk) {
