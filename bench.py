@@ -8,9 +8,10 @@ all inputs resident in HBM.  Prints ONE JSON line:
   value      whole-step fp32 throughput in TFLOP/s (sum of the operators' algorithmic
              FLOPs / step time), buffers rotated between steps so that a step does not
              find its inputs in the 256 MB Infinity Cache of the previous one;
-  per_op     every operator's own launch time (HIP events on the launch stream), warm
-             (same buffers) and cold (rotating buffer sets), TFLOP/s against the
-             157.3 TFLOP/s fp32 MFMA peak and GB/s against 8 TB/s;
+  per_op     every operator's own launch time (HIP events on the launch stream around a
+             replayed HIP graph of 24 launches), warm (same buffers) and cold (12 rotating
+             buffer sets), TFLOP/s against the 157.3 TFLOP/s fp32 MFMA peak and GB/s
+             against 8 TB/s; us_cold_eager is the same launch issued from Python;
   roofline   the dominant kernel (the implicit-GEMM convolution on its largest launch);
   cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample.
 
@@ -117,6 +118,32 @@ def time_launches(torch, fn, reps):
     return start.elapsed_time(end) * 1000.0 / reps
 
 
+def time_graph(torch, fn, launches, replays=10):
+    """Average time of one call of fn in microseconds when `launches` calls are captured in one
+    HIP graph (no host launch overhead between kernels) and the graph is replayed."""
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        for i in range(launches):       # warm-up on the capture stream, outside the capture
+            fn(i)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(launches):
+                fn(i)
+        graph.replay()
+        stream.synchronize()
+        start = torch.cuda.Event(enable_timing=True)
+        end = torch.cuda.Event(enable_timing=True)
+        start.record(stream)
+        for _ in range(replays):
+            graph.replay()
+        end.record(stream)
+        stream.synchronize()
+    torch.cuda.current_stream().wait_stream(stream)
+    return start.elapsed_time(end) * 1000.0 / (launches * replays)
+
+
 def oracle_reference(I, host, name):
     import oracle
     c = host[name]
@@ -162,6 +189,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing and parity check (profiling runs)")
     ap.add_argument("--only", default=None, help="profiling aid: launch only this operator in the step")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU figures are not produced",
@@ -174,6 +204,16 @@ def main():
         sys.exit(1)
     from paper_2006_06762_amd import binding as anr
     from paper_2006_06762_amd import inputs as I
+
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.ones(n // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_each_way": n, "copies": 10}))
+        return
 
     table = workload_table(I)
     host = {name: I.config_inputs(name) for name in I.CONFIG_NAMES}
@@ -208,10 +248,13 @@ def main():
         reps = 200
         for i in range(10):
             sets[0].run(n)
-        warm = time_launches(torch, lambda i: sets[0].run(n), reps)
-        cold = time_launches(torch, lambda i: sets[i % NSETS].run(n), reps)
+        # launches captured in a HIP graph: kernel time plus the GPU's own kernel-to-kernel gap
+        warm = time_graph(torch, lambda i: sets[0].run(n), 2 * NSETS)
+        cold = time_graph(torch, lambda i: sets[i % NSETS].run(n), 2 * NSETS)
+        # the same launches issued one by one from Python (adds host launch overhead)
+        eager = time_launches(torch, lambda i: sets[i % NSETS].run(n), reps)
         rec = {"op": n, "bound": bound, "flops": flops, "bytes": nbytes,
-               "us_warm": warm, "us_cold": cold,
+               "us_warm": warm, "us_cold": cold, "us_cold_eager": eager,
                "tflops_warm": flops / warm / 1e6, "tflops_cold": flops / cold / 1e6,
                "gbs_warm": nbytes / warm / 1e3, "gbs_cold": nbytes / cold / 1e3}
         rec["frac_mfma_peak_warm"] = rec["tflops_warm"] / PEAK_MFMA_F32_TFLOPS

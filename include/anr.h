@@ -24,7 +24,8 @@
  *     version); ws may be NULL when that is 0.
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is launched, so an invalid call has no effect on the device.
- *   - Thread-safe and re-entrant: there is no mutable global state.
+ *   - Thread-safe and re-entrant: the only state is a thread-local copy of the last
+ *     HIP launch error, kept for anr_last_hip_error().
  */
 #ifndef ANR_H
 #define ANR_H
@@ -139,8 +140,9 @@ anr_status anr_dwconv(const anr_conv_desc *desc, const float *x, const float *w,
 anr_status anr_tbg(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Full TBS (Sec. 7.2, Appendix C "TBS"): anr_tbg followed by a softmax over j,
- * fused in the same kernel.  Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
+/* Full TBS (Sec. 7.2, Appendix C "TBS"): anr_tbg followed by a softmax over j
+ * (max-subtracted, in place on `out`, a second kernel on the same stream).
+ * Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
 anr_status anr_tbs(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
