@@ -90,15 +90,19 @@ struct Geom {
     int vec_store;  // 4 consecutive pixels of a lane are 16 contiguous, aligned bytes of y
     int ohow;       // OH*OW
     FastDiv d_ow, d_oh, d_hv, d_w4, d_perc, d_ohow, d_units;   // divisors OW, OH, HV, W4, VR*W4, OH*OW, n_units
+    // work-group id -> tile: ids are dealt round-robin over the 8 XCDs, so id % 8 picks a
+    // rectangle of (tiles_m / xcd_m) x (tiles_n / xcd_n) tiles that one XCD's L2 serves
+    int tiles_m, tiles_n, xcd_m, xcd_n;
+    FastDiv d_sub_n;            // divisor tiles_n / xcd_n
 #ifdef ANR_IGEMM_TRACE
     long long* trace;   // experiment harness only: per-work-group phase timestamps
 #endif
 };
 
 #ifdef ANR_IGEMM_TRACE
-#define ANR_TRACE(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
+#define ANR_TRACE(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
 #define ANR_TRACE_END(slot) do { __builtin_amdgcn_s_waitcnt(0); ANR_TRACE(slot); } while (0)
-#define ANR_TRACE_CLK(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = clock64(); } while (0)
+#define ANR_TRACE_CLK(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = clock64(); } while (0)
 #else
 #define ANR_TRACE_CLK(slot) do { } while (0)
 #define ANR_TRACE(slot) do { } while (0)
@@ -149,7 +153,21 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     const int r32 = lane & 31, h = lane >> 5;
     const int tile_wave = wave % (WAVES_M * WAVES_N), ks = wave / (WAVES_M * WAVES_N);
     const int wave_m = tile_wave / WAVES_N, wave_n = tile_wave % WAVES_N;
-    const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+    int tile_m, tile_n;
+    {
+        const int w = blockIdx.x;
+        if (g.xcd_m * g.xcd_n == 8) {
+            const int xcd = w & 7, slot = w >> 3;
+            const int sub_m = g.tiles_m / g.xcd_m, sub_n = g.tiles_n / g.xcd_n;
+            const int lm = g.d_sub_n.div(slot);
+            tile_m = (xcd / g.xcd_n) * sub_m + lm;
+            tile_n = (xcd % g.xcd_n) * sub_n + (slot - lm * sub_n);
+        } else {
+            tile_m = w % g.tiles_m;
+            tile_n = w / g.tiles_m;
+        }
+    }
+    const int m0 = tile_m * BM, co0 = tile_n * BN;
 
     const int g0 = g.d_ow.div(m0);
     const int n_first = g.d_oh.div(g0);
@@ -426,6 +444,27 @@ struct Variant {
         g->d_perc = make_fastdiv(g->VR * g->W4);
         g->d_ohow = make_fastdiv(g->ohow);
         g->d_units = make_fastdiv(g->n_units);
+        // XCD-aware tile mapping: split the tile grid 8 ways (xcd_m x xcd_n) so that the bytes one
+        // XCD has to pull through its L2 (its share of x plus its share of w) are smallest
+        g->tiles_m = (g->Mtot + BM - 1) / BM;
+        g->tiles_n = (a.K + BN - 1) / BN;
+        if ((int64_t)g->tiles_m * g->tiles_n >= ((int64_t)1 << 31)) return false;
+        g->xcd_m = g->xcd_n = 0;
+        {
+            const double xb = (double)a.N * a.C * a.H * a.W, wb = (double)a.K * a.C * a.R * a.S;
+            double best = 0.0;
+            for (int xm = 1; xm <= 8; xm *= 2) {
+                const int xn = 8 / xm;
+                if (g->tiles_m % xm != 0 || g->tiles_n % xn != 0) continue;
+                const double bytes = xb / xm + wb / xn;
+                if (g->xcd_m == 0 || bytes < best) {
+                    best = bytes;
+                    g->xcd_m = xm;
+                    g->xcd_n = xn;
+                }
+            }
+        }
+        g->d_sub_n = make_fastdiv(g->xcd_n ? g->tiles_n / g->xcd_n : 1);
         size_t floats = 2 * ((size_t)CK * g->P + (size_t)BN * WS);
         // the k-split reduction reuses the staging memory
         const size_t red = (size_t)(KSPLIT - 1) * WAVES_M * WAVES_N * WM_BLK * WN_BLK * 64 * 16;
@@ -443,7 +482,7 @@ struct Variant {
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
             if (e != hipSuccess) return e;
         }
-        dim3 grid((g.Mtot + BM - 1) / BM, (a.K + BN - 1) / BN);
+        dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
         return launch_kernel(kern, grid, dim3(NT), lds_bytes, stream, a, g);
     }
 
