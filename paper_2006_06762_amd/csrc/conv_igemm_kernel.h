@@ -103,7 +103,15 @@ struct Geom {
 #define ANR_TRACE(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
 #define ANR_TRACE_END(slot) do { __builtin_amdgcn_s_waitcnt(0); ANR_TRACE(slot); } while (0)
 #define ANR_TRACE_CLK(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = clock64(); } while (0)
+#define ANR_PHASE_DECL long long ph_t = 0, ph_acc[4] = {0, 0, 0, 0}
+#define ANR_PHASE_START do { ph_t = clock64(); } while (0)
+#define ANR_PHASE(k) do { long long now_ = clock64(); ph_acc[k] += now_ - ph_t; ph_t = now_; } while (0)
+#define ANR_PHASE_FLUSH do { if ((threadIdx.x & 63) == 0 && g.trace) { long long* d_ = g.trace + (long long)gridDim.x * 8 + (blockIdx.x * 16 + (threadIdx.x >> 6)) * 4; for (int k_ = 0; k_ < 4; ++k_) d_[k_] = ph_acc[k_]; } } while (0)
 #else
+#define ANR_PHASE_DECL
+#define ANR_PHASE_START do { } while (0)
+#define ANR_PHASE(k) do { } while (0)
+#define ANR_PHASE_FLUSH do { } while (0)
 #define ANR_TRACE_CLK(slot) do { } while (0)
 #define ANR_TRACE(slot) do { } while (0)
 #define ANR_TRACE_END(slot) do { } while (0)
@@ -266,6 +274,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     ANR_TRACE(2);
     ANR_TRACE_CLK(6);
 
+    ANR_PHASE_DECL;
     // One chunk: MFMAs on LDS buffer `buf`, staging of chunk cc+1 into the other buffer.
     auto chunk = [&](int cc, auto buf_c) {
         constexpr int buf = decltype(buf_c)::value;
@@ -286,9 +295,12 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             for (int nb = 0; nb < WN_BLK; ++nb)
                 b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + rd_b);
         };
+        ANR_PHASE_START;
         read_step(0, a_cur, b_cur);
 #pragma unroll
         for (int t = 0; t < SPW; ++t) {
+            if (t == 1) ANR_PHASE(0);
+            if (t == SPW - 1) ANR_PHASE(1);
             // reads of step t+1 are issued before the MFMAs of step t: their latency hides
             // behind those MFMAs instead of stalling the next ones
             if (t + 1 < SPW) read_step(t + 1, a_nxt, b_nxt);
@@ -308,13 +320,16 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
 #pragma unroll
             for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
         }
+        ANR_PHASE(2);
         __syncthreads();
+        ANR_PHASE(3);
     };
     for (int cc = 0; cc < nchunks; cc += 2) {
         chunk(cc, std::integral_constant<int, 0>{});
         if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
     }
 
+    ANR_PHASE_FLUSH;
     ANR_TRACE(3);
     ANR_TRACE_CLK(7);
     // ---- reduce-scatter of the k-split partial accumulators: block b belongs to wave ks == b % KSPLIT
