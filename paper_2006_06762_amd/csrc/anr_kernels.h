@@ -23,6 +23,8 @@ inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, s
     return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, lds_bytes, stream);
 }
 
+inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 // Batched C = A.B (B_IS_NK false: B is K x N, row stride ldb) or C = A.B^T
 // (B_IS_NK true: B is N x K, row stride ldb).  Batch index z in [0, batch) is
 // split as z = zo*batch_inner + zi, and operand X starts at

@@ -14,6 +14,4 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
 // Register-sliding 3x3 / stride 1 / pad 1 depthwise kernel; same contract.
 hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken);
 
-inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
 }  // namespace anr

@@ -392,7 +392,6 @@ hipError_t launch_variant(const GemmArgs& a, hipStream_t stream)
     return launch_kernel(gemm_kernel<BM, BN, BK, NT, VEC>, grid, dim3(256), 0, stream, a);
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
 
@@ -400,7 +399,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
 {
     const bool strides4 = (a.sAo % 4 == 0) && (a.sAi % 4 == 0) && (a.sBo % 4 == 0) &&
                           (a.sBi % 4 == 0) && (a.sCo % 4 == 0) && (a.sCi % 4 == 0);
-    bool vec = aligned16(a.A) && aligned16(a.B) && aligned16(a.C) && strides4 &&
+    bool vec = is_aligned16(a.A) && is_aligned16(a.B) && is_aligned16(a.C) && strides4 &&
                (a.K % 4 == 0) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) && (a.ldc % 4 == 0);
     if (!a.b_is_nk) vec = vec && (a.N % 4 == 0);
 
@@ -410,7 +409,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
     // few tiles and a long reduction: one 32x32 tile per work-group, K split over its waves
     const int64_t tiles32 = (int64_t)(a.M / 32) * (a.N / 32) * a.batch;
     if (!a.b_is_nk && !a.softmax_rows && (a.M % 32 == 0) && (a.N % 32 == 0) && tiles32 <= 1024 &&
-        a.batch_inner == 1 && aligned16(a.A) && aligned16(a.B) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) &&
+        a.batch_inner == 1 && is_aligned16(a.A) && is_aligned16(a.B) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) &&
         (a.sAo % 4 == 0) && (a.sBo % 4 == 0) && a.batch <= 65535) {
         if (a.K == 256) return launch_ksplit<2>(a, stream);
         if (a.K == 512) return launch_ksplit<4>(a, stream);

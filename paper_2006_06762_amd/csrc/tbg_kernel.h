@@ -11,6 +11,14 @@
 // multiplies one 32 x 32 block with v_mfma_f32_32x32x2_f32, reading both operands from
 // LDS with 16-byte reads (rows of q and k are both contiguous in d, so A and B use the
 // same layout and a half-wave takes four consecutive d per read).
+//
+// Two restructurings were measured and dropped: one persistent work-group per CU that
+// prefetches tile t+1 while multiplying tile t (11.9 us against 8.8 us: a single tile of
+// look-ahead does not cover the ~2 us loaded memory latency), and one work-group per CU
+// that requests the panels of its three tiles at once and shares panels between them
+// (10.8 us: a CU ingests only ~10 bytes per clock from cold HBM, and a wave that is stuck
+// issuing loads cannot multiply).  Three independent work-groups per CU keep more requests
+// in flight and win.
 #pragma once
 #include "anr_device.h"
 #include "anr_kernels.h"
@@ -31,18 +39,32 @@ struct Args {
     int64_t ks_b, ks_s, ks_h;
     int64_t os_b, os_h, os_i;   // element strides of out [b, h, i, j] (j stride 1)
     int tiles_i, tiles_j;       // ceil(S / 64) each
+    int xcd_chunk;              // tiles per XCD when the tile count is a multiple of 8, else 0
 };
+
+#ifdef ANR_TBG_TRACE
+__device__ long long* anr_tbg_trace = nullptr;
+#define TT(slot) do { if (threadIdx.x == 0 && anr_tbg_trace) anr_tbg_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#define TT_END(slot) do { __builtin_amdgcn_s_waitcnt(0); TT(slot); } while (0)
+#else
+#define TT(slot) do { } while (0)
+#define TT_END(slot) do { } while (0)
+#endif
 
 __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
 {
+    TT(0);
     __shared__ __attribute__((aligned(16))) float qs[kTile * kLds];
     __shared__ __attribute__((aligned(16))) float ks[kTile * kLds];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int r32 = lane & 31, h2 = lane >> 5;
-    // blockIdx.x = ((b*H + h) * tiles_i + ti) * tiles_j + tj
+    // tile id = ((b*H + h) * tiles_i + ti) * tiles_j + tj.  Work-group ids are dealt round-robin
+    // over the 8 XCDs; give every XCD a contiguous range of tile ids, so that the tiles of one
+    // score matrix, which share their q and k panels, meet in one L2.
     int t = blockIdx.x;
+    if (p.xcd_chunk > 0) t = (t & 7) * p.xcd_chunk + (t >> 3);
     const int tj = t % p.tiles_j; t /= p.tiles_j;
     const int ti = t % p.tiles_i; t /= p.tiles_i;
     const int hh = t % p.H, b = t / p.H;
@@ -73,6 +95,7 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             rq[u] = ldg4(qb + ri * p.qs_s + dd);
             rk[u] = ldg4(kb + rj * p.ks_s + dd);
         }
+        TT(1);
         if (d0 > 0) __syncthreads();             // previous chunk fully consumed
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -80,6 +103,7 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             *reinterpret_cast<f32x4*>(&ks[(srow + 16 * u) * kLds + sd]) = din ? rk[u] : zero4();
         }
         __syncthreads();
+        TT(2);
 
         f32x4 a[8], bb[8];
 #pragma unroll
@@ -97,6 +121,7 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
+    TT(3);
 
     // register r of lane (h2, r32): row 8*(r/4) + 4*h2 + r%4, column r32 of the block
     float* __restrict__ ob = p.out + b * p.os_b + hh * p.os_h;
@@ -108,6 +133,7 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             if (row < p.S) ob[row * p.os_i + col] = acc[r];
         }
     }
+    TT_END(4);
 }
 
 }  // namespace tbg
