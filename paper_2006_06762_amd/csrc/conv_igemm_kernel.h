@@ -93,6 +93,7 @@ struct Geom {
     // work-group id -> tile: ids are dealt round-robin over the 8 XCDs, so id % 8 picks a
     // rectangle of (tiles_m / xcd_m) x (tiles_n / xcd_n) tiles that one XCD's L2 serves
     int tiles_m, tiles_n, xcd_m, xcd_n;
+    uint32_t x_bytes, w_bytes;   // extents of the x view and of w, for the buffer descriptors
     FastDiv d_sub_n;            // divisor tiles_n / xcd_n
 #ifdef ANR_IGEMM_TRACE
     long long* trace;   // experiment harness only: per-work-group phase timestamps
@@ -243,10 +244,18 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     f32x4 rx[XU], rw[WU];
     const int nchunks = p.C / CK;
 
-    // staging unit j: global -> registers (uniform 64-bit base + 32-bit per-lane byte offset)
-    auto side_load = [&](int j, const char* __restrict__ xb, const char* __restrict__ wb) {
-        if (j < XU) rx[j] = *reinterpret_cast<const f32x4*>(xb + xoff[j]);
-        else rw[j - XU] = *reinterpret_cast<const f32x4*>(wb + woff[j - XU]);
+    // staging unit j: global -> registers.  Buffer loads: the descriptor (base, extent) sits in
+    // scalar registers for the whole kernel, the lane supplies a 32-bit byte offset and the chunk
+    // a scalar one, so a load needs no vector ALU work for its address.
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
+    auto side_load = [&](int j, uint32_t xchunk_b, uint32_t wchunk_b) {
+        if (j < XU)
+            rx[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)xoff[j], (int)xchunk_b, 0));
+        else
+            rw[j - XU] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff[j - XU], (int)wchunk_b, 0));
     };
     // staging unit j: registers -> LDS, xbuf_b / wbuf_b = byte offset of the target buffer
     auto side_store = [&](int j, int xbuf_b, int wbuf_b) {
@@ -263,8 +272,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
 
     ANR_TRACE(1);
 #pragma unroll
-    for (int j = 0; j < NSIDE; ++j)
-        side_load(j, reinterpret_cast<const char*>(p.x), reinterpret_cast<const char*>(p.w));
+    for (int j = 0; j < NSIDE; ++j) side_load(j, 0u, 0u);
     for (int idx = tid; idx < (2 * patch_sz) / 4; idx += NT)
         reinterpret_cast<f32x4*>(smem)[idx] = zero4();
     __syncthreads();
@@ -280,8 +288,8 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         constexpr int buf = decltype(buf_c)::value;
         // the chunk after the last one is the last one again: loaded and stored, never read
         const int cn = cc + 1 < nchunks ? cc + 1 : cc;
-        const char* __restrict__ xb = reinterpret_cast<const char*>(p.x + (int64_t)cn * CK * p.xs[1]);
-        const char* __restrict__ wb = reinterpret_cast<const char*>(p.w + (int64_t)cn * KC);
+        const uint32_t xb = 4u * (uint32_t)cn * (uint32_t)(CK * p.xs[1]);     // byte offset of the chunk
+        const uint32_t wb = 4u * (uint32_t)cn * (uint32_t)KC;
         const int rd_a = 4 * buf * patch_sz, rd_b = 4 * buf * WTS_SZ;
         const int st_a = 4 * (buf ^ 1) * patch_sz, st_b = 4 * (buf ^ 1) * WTS_SZ;
 
@@ -431,6 +439,10 @@ struct Variant {
     static constexpr int BM = 32 * WM_BLK * WAVES_M, BN = 32 * WN_BLK * WAVES_N;
     static constexpr int CK = 2 * CPH;
     static constexpr int WS = CK * R_ * S_ + 2;
+    // staging units per thread the main loop can hide: half of a wave's MFMAs per chunk carry one
+    static constexpr int WU = (BN * (CK * R_ * S_ / 4) + NT - 1) / NT;
+    static constexpr int SLOTS = (CPH * R_ * S_ / KSPLIT) * WM_BLK * WN_BLK;
+    static constexpr int kMaxXU = (SLOTS / 2 - WU) < kMaxUnits ? (SLOTS / 2 - WU) : kMaxUnits;
 
     // Fills the geometry; false if this variant cannot run the problem.
     static bool plan(const ConvArgs& a, Geom* g, size_t* lds_bytes)
@@ -447,7 +459,7 @@ struct Variant {
         g->P = g->VR * g->RSL;
         g->W4 = a.W / 4;
         g->n_units = CK * g->VR * g->W4;
-        if (g->n_units > kMaxUnits * NT) return false;
+        if (kMaxXU < 1 || g->n_units > kMaxXU * NT) return false;
         // virtual row numbers must stay below 2^31 for the fast division
         if ((int64_t)a.N * g->HV + g->VR >= ((int64_t)1 << 31)) return false;
         g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) &&
@@ -459,6 +471,9 @@ struct Variant {
         g->d_perc = make_fastdiv(g->VR * g->W4);
         g->d_ohow = make_fastdiv(g->ohow);
         g->d_units = make_fastdiv(g->n_units);
+        g->x_bytes = (uint32_t)(4 * ((int64_t)(a.N - 1) * a.xs[0] + (int64_t)(a.C - 1) * a.xs[1] +
+                                     (int64_t)(a.H - 1) * a.xs[2] + a.W));
+        g->w_bytes = (uint32_t)(4 * (int64_t)a.K * a.C * a.R * a.S);
         // XCD-aware tile mapping: split the tile grid 8 ways (xcd_m x xcd_n) so that the bytes one
         // XCD has to pull through its L2 (its share of x plus its share of w) are smallest
         g->tiles_m = (g->Mtot + BM - 1) / BM;
@@ -515,10 +530,17 @@ struct Variant {
     static hipError_t launch(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
     {
         const int per_thread = units_per_thread(g);
-        if (per_thread <= 2) return launch_inst<2, 0, 0>(a, g, lds_bytes, stream);
-        if (per_thread <= 4) return launch_inst<4, 0, 0>(a, g, lds_bytes, stream);
-        if (per_thread <= 6) return launch_inst<6, 0, 0>(a, g, lds_bytes, stream);
-        return launch_inst<kMaxUnits, 0, 0>(a, g, lds_bytes, stream);
+        if constexpr (kMaxXU >= 2) {
+            if (per_thread <= 2) return launch_inst<2, 0, 0>(a, g, lds_bytes, stream);
+        }
+        if constexpr (kMaxXU >= 4) {
+            if (per_thread <= 4) return launch_inst<4, 0, 0>(a, g, lds_bytes, stream);
+        }
+        if constexpr (kMaxXU >= 6) {
+            if (per_thread <= 6) return launch_inst<6, 0, 0>(a, g, lds_bytes, stream);
+        }
+        if constexpr (kMaxXU >= 1) return launch_inst<kMaxXU, 0, 0>(a, g, lds_bytes, stream);
+        return hipErrorInvalidValue;     // unreachable: plan() rejects variants with kMaxXU < 1
     }
 
     // Relative cost: rounds of work-groups over the 256 CUs times the tile volume.

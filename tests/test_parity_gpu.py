@@ -123,6 +123,12 @@ CONV_FAST = [
     I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 1), (0, 0)),
     I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 2), (2, 1)),
     I.ConvShape(1, 32, 56, 56, 64, 3, 3, (1, 1), (1, 1)),
+    # pointwise (1x1) MFMA path: C % 32 == 0, W % 4 == 0
+    I.ConvShape(2, 32, 12, 12, 40, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(3, 64, 8, 8, 70, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(1, 64, 56, 56, 64, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(2, 32, 12, 16, 16, 1, 1, (2, 2), (0, 0)),
+    I.ConvShape(1, 96, 9, 8, 33, 1, 1, (1, 1), (1, 1)),
 ]
 # everything else goes through the direct kernel
 CONV_GENERIC = [
