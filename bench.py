@@ -52,7 +52,14 @@ def workload_table(I):
                 "mfma"),
         "DEP": (2.0 * d.N * d.C * d.OH * d.OW * 9, 4.0 * (2 * d.N * d.C * d.H * d.W + d.C * 9), "hbm"),
         "C2D_S2": (conv_flops(I.C2D_S2), conv_bytes(I.C2D_S2), "mfma"),
+        # TBS = TBG with the row softmax fused in: the matmul's flops (the softmax's ~5 S^2 per
+        # head are not counted), the same compulsory bytes
+        "TBS": (2.0 * t.B * t.H * t.S * t.S * t.D, 4.0 * (2 * t.B * t.S * t.H * t.D + t.B * t.H * t.S * t.S),
+                "mfma"),
     }
+
+
+EXTRA_OPS = ("TBS",)       # measured on their own, not part of the step
 
 
 class OpSet:
@@ -79,7 +86,7 @@ class OpSet:
         self.I = I
 
     def run(self, name):
-        a, t, I = self.anr, self.t[name], self.I
+        a, t, I = self.anr, self.t["TBG" if name == "TBS" else name], self.I
         if name == "GMM":
             a.gemm(t["A"], t["B"], t["C"])
         elif name == "C2D":
@@ -89,6 +96,8 @@ class OpSet:
                            I.CONVLAYER.stride, I.CONVLAYER.pad)
         elif name == "TBG":
             a.tbg(t["q"], t["k"], t["out"])
+        elif name == "TBS":
+            a.tbs(t["q"], t["k"], t["out"])
         elif name == "DEP":
             a.dwconv(t["x"], t["w"], t["y"], I.DEP.stride, I.DEP.pad)
         elif name == "C2D_S2":
@@ -97,7 +106,7 @@ class OpSet:
             raise KeyError(name)
 
     def output(self, name):
-        t = self.t[name]
+        t = self.t["TBG" if name == "TBS" else name]
         return t.get("y", t.get("C", t.get("out")))
 
     def step(self):
@@ -146,7 +155,7 @@ def time_graph(torch, fn, launches, replays=10):
 
 def oracle_reference(I, host, name):
     import oracle
-    c = host[name]
+    c = host["TBG" if name == "TBS" else name]
     s = c["shape"]
     if name == "GMM":
         return oracle.gemm(c["A"], c["B"])
@@ -157,6 +166,8 @@ def oracle_reference(I, host, name):
                                    s.stride, s.pad)
     if name == "TBG":
         return oracle.tbg(c["q"], c["k"])
+    if name == "TBS":
+        return oracle.tbs(c["q"], c["k"])
     if name == "DEP":
         return oracle.dwconv(c["x"], c["w"], s.stride, s.pad)
     raise KeyError(name)
@@ -243,7 +254,8 @@ def main():
 
     # per-operator launch times
     per_op = []
-    for n in names:
+    measured = tuple(names) + (EXTRA_OPS if args.only is None else ())
+    for n in measured:
         flops, nbytes, bound = table[n]
         reps = 200
         for i in range(10):
@@ -260,6 +272,7 @@ def main():
         rec["frac_mfma_peak_warm"] = rec["tflops_warm"] / PEAK_MFMA_F32_TFLOPS
         rec["frac_mfma_peak_cold"] = rec["tflops_cold"] / PEAK_MFMA_F32_TFLOPS
         rec["frac_hbm_peak_cold"] = rec["gbs_cold"] / PEAK_HBM_GBS
+        rec["in_step"] = n in names
         per_op.append(rec)
 
     by = {r["op"]: r for r in per_op}
@@ -297,7 +310,9 @@ def main():
         refs, base = cpu_baseline(I, host, table)
         out["cpu_baseline"] = base
         errs = {}
-        for n in names:
+        for n in EXTRA_OPS:
+            refs[n] = oracle_reference(I, host, n)      # outside the timed oracle pass
+        for n in measured:
             sets[0].run(n)
             got = sets[0].output(n).cpu().numpy().astype(np.float64)
             errs[n] = float(np.max(np.abs(got - refs[n]) / np.maximum(1.0, np.abs(refs[n]))))

@@ -3,6 +3,29 @@
 #include "tbg_kernel.h"
 
 namespace anr {
+namespace {
+
+template <int UT, int QB>
+hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipStream_t stream)
+{
+    tbg::Args t = t0;
+    const int rows_q = 32 * QB, ld = t.D + 4;
+    t.tiles_i = (t.S + rows_q - 1) / rows_q;
+    // q rows, then the k panel, which the staged probabilities (rows_q x kLdP) later overwrite
+    const size_t kpanel = (size_t)tbg::kRowsKeys * ld, probs = (size_t)rows_q * tbg::kLdP;
+    const size_t lds_bytes = sizeof(float) * ((size_t)rows_q * ld + (kpanel > probs ? kpanel : probs));
+    auto kern = tbg::tbs_rows32_kernel<UT, true, QB>;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    return launch_kernel(kern, dim3((unsigned)(batch * t.tiles_i)), dim3(256 * QB), lds_bytes, stream, t, ld,
+                         vec_store);
+}
+
+}  // namespace
+
 hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream)
 {
     // a describes out[z] = A[z] . B[z]^T with z = (b, h): see GemmArgs
@@ -23,6 +46,13 @@ hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream)
     t.os_b = a.sCo; t.os_h = a.sCi; t.os_i = a.ldc;
     t.tiles_i = tiles; t.tiles_j = tiles;
     t.xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
+    if (a.softmax_rows && a.M <= tbg::kRowsKeys && a.K <= 128 && (a.K % 8 == 0)) {
+        // fused TBS: 32 query rows x all keys per work-group
+        const int vec_store = is_aligned16(a.C) && (a.ldc % 4 == 0) && (a.sCo % 4 == 0) && (a.sCi % 4 == 0);
+        if (a.K <= 32) return launch_tbs_rows32<5, 1>(t, a.batch, vec_store, stream);
+        if (a.K <= 64) return launch_tbs_rows32<10, 1>(t, a.batch, vec_store, stream);
+        return launch_tbs_rows32<20, 1>(t, a.batch, vec_store, stream);
+    }
     hipError_t err = launch_kernel(tbg::tbg_tile_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t);
     if (err != hipSuccess || !a.softmax_rows) return err;
     return launch_softmax_rows(a, stream);

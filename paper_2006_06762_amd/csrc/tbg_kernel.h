@@ -136,5 +136,152 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
     TT_END(4);
 }
 
+// ---------------------------------------------------------------------------------------
+// Full TBS for S <= 128: the batch matmul with the row softmax fused (Sec. 7.2: two
+// transposes, one batch matmul, one softmax), so a row of scores never leaves the chip
+// before it is normalised.
+//
+// Work-group = 32 queries x ALL keys of one (b, h); wave w owns keys 32w .. 32w + 31.  The
+// benchmark shape gives 768 work-groups = 3 per CU, 3 waves on every SIMD.  The q rows and
+// the k panel are staged in LDS with fully coalesced 16-byte loads (loading the MFMA operand
+// registers straight from global memory was measured at 14.3 us for the matmul alone: a lane
+// is a matrix row there, so every request touches 32 cache lines for 32 bytes each).
+//
+// The wave computes the TRANSPOSED block  T = k_blk . q_blk^T  (keys are MFMA rows, queries
+// MFMA columns).  In the accumulator layout of v_mfma_f32_32x32x2_f32 a lane then holds 16
+// keys of ONE query, so a softmax row reduces inside the lane: 15 max / add operations, one
+// exchange with the other half-wave, one exchange through LDS between the four waves.  The
+// probabilities go back through LDS (over the k panel) so that each store instruction writes
+// two complete output rows.
+//
+// UT = 16-byte staging units per thread: ceil(160 * (D/4) / 256).
+constexpr int kRowsKeys = 128;
+constexpr int kLdP = kRowsKeys + 4;       // row stride of the staged probabilities
+
+template <int UT, bool SOFTMAX, int QB>
+__global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int ld, int vec_store)
+{
+    extern __shared__ __attribute__((aligned(16))) float panel[];   // q rows 0..31, then k rows 0..127
+    constexpr int kRowsQ = 32 * QB, NT = 256 * QB;
+    __shared__ float red[2][QB][4][32];
+    float* const qs = panel;
+    float* const ks = panel + kRowsQ * ld;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int wave = wv & 3, qblk = wv >> 2;    // key block, query block
+    const int r32 = lane & 31, h2 = lane >> 5;
+    // blockIdx.x = (b*H + h) * tiles_i + ti, tiles_i = ceil(S / 32)
+    const int ti = blockIdx.x % p.tiles_i;
+    const int bh = blockIdx.x / p.tiles_i;
+    const int hh = bh % p.H, b = bh / p.H;
+    const int i0 = ti * kRowsQ;
+
+    const float* __restrict__ qb = p.q + b * p.qs_b + hh * p.qs_h;
+    const float* __restrict__ kb = p.k + b * p.ks_b + hh * p.ks_h;
+
+    // staging unit u of thread tid: unit index tid + 256*u of the 160 x (D/4) panel, walked
+    // without a division per unit
+    const int dq = p.D >> 2;
+    const int row_step = NT / dq, col_step = NT - row_step * dq;
+    const int rows_all = kRowsQ + kRowsKeys;
+    int srow = tid / dq, scol = tid - srow * dq;
+    f32x4 rg[UT];
+    int lds_off[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+        const int row = srow < rows_all ? srow : rows_all - 1;      // surplus units repeat the last row
+        const bool isq = row < kRowsQ;
+        // rows past S re-read row S-1; what they produce is masked or never stored
+        int gr = isq ? i0 + row : row - kRowsQ;
+        gr = gr < p.S ? gr : p.S - 1;
+        const float* src = isq ? qb + gr * p.qs_s : kb + gr * p.ks_s;
+        rg[u] = ldg4(src + 4 * scol);
+        lds_off[u] = row * ld + 4 * scol;
+        srow += row_step;
+        scol += col_step;
+        if (scol >= dq) { scol -= dq; ++srow; }
+    }
+#pragma unroll
+    for (int u = 0; u < UT; ++u) *reinterpret_cast<f32x4*>(&panel[lds_off[u]]) = rg[u];
+    __syncthreads();
+
+    f32x16 acc, acc2;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
+    const float* arow = ks + (32 * wave + r32) * ld + 4 * h2;
+    const float* brow = qs + (32 * qblk + r32) * ld + 4 * h2;
+    for (int d0 = 0; d0 < p.D; d0 += 8) {               // D is a multiple of 8
+        const f32x4 a = *reinterpret_cast<const f32x4*>(arow + d0);
+        const f32x4 bq = *reinterpret_cast<const f32x4*>(brow + d0);
+        acc = mfma32(a[0], bq[0], acc);
+        acc2 = mfma32(a[1], bq[1], acc2);
+        acc = mfma32(a[2], bq[2], acc);
+        acc2 = mfma32(a[3], bq[3], acc2);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
+
+    // register r of lane (h2, r32): key 32*wave + 8*(r/4) + 4*h2 + r%4, query i0 + 32*qblk + r32
+    const int key0 = 32 * wave + 4 * h2;
+    if (SOFTMAX) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool in = key0 + 8 * (r / 4) + (r % 4) < p.S;
+            acc[r] = in ? acc[r] : -INFINITY;
+            mx = fmaxf(mx, acc[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (h2 == 0) red[0][qblk][wave][r32] = mx;
+        __syncthreads();
+        // key 0 is always inside, so the maximum over the four key blocks is finite
+        mx = fmaxf(fmaxf(red[0][qblk][0][r32], red[0][qblk][1][r32]), fmaxf(red[0][qblk][2][r32], red[0][qblk][3][r32]));
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc[r] = __expf(acc[r] - mx);                // exp(-inf) = 0 for masked keys
+            sum += acc[r];
+        }
+        sum += __shfl_xor(sum, 32);
+        if (h2 == 0) red[1][qblk][wave][r32] = sum;
+        __syncthreads();
+        sum = (red[1][qblk][0][r32] + red[1][qblk][1][r32]) + (red[1][qblk][2][r32] + red[1][qblk][3][r32]);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] *= inv;
+    } else {
+        __syncthreads();                                 // every wave is done reading the k panel
+    }
+
+    // transpose through LDS: P[query][key], over the k panel (the launch sizes LDS for both)
+    float* const ps = ks;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        f32x4 v;
+        v[0] = acc[4 * g]; v[1] = acc[4 * g + 1]; v[2] = acc[4 * g + 2]; v[3] = acc[4 * g + 3];
+        *reinterpret_cast<f32x4*>(&ps[(32 * qblk + r32) * kLdP + key0 + 8 * g]) = v;
+    }
+    __syncthreads();
+    float* __restrict__ ob = p.out + b * p.os_b + hh * p.os_h;
+    const int col = 4 * r32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rl = 8 * wv + 2 * i + h2;
+        const int row = i0 + rl;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&ps[rl * kLdP + col]);
+        if (row < p.S) {
+            float* orow = ob + row * p.os_i;
+            if (vec_store && col + 3 < p.S) {
+                stg4(orow + col, v);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < p.S) orow[col + e] = v[e];
+            }
+        }
+    }
+}
+
 }  // namespace tbg
 }  // namespace anr
