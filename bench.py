@@ -153,6 +153,60 @@ def time_graph(torch, fn, launches, replays=10):
     return start.elapsed_time(end) * 1000.0 / (launches * replays)
 
 
+def shape_list(anr, I, torch):
+    """Launch times of every Appendix C shape at batch 1 and 16 (operator and subgraph benchmarks,
+    Sec. 7.1 and 7.2).  Timing only: values are uniform random numbers drawn on the device."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(I.SEED_BASE)
+    rnd = lambda *shape: torch.rand(shape, generator=gen, device="cuda", dtype=torch.float32) * 2 - 1
+    emp = lambda *shape: torch.empty(shape, device="cuda", dtype=torch.float32)
+    rows = []
+    for op in ("GMM", "C2D", "DEP", "ConvLayer", "TBS"):
+        for fields in I.APPENDIX_C[op]:
+            for batch in I.BATCHES:
+                s = I.appendix_shape(op, fields, batch)
+                if op == "GMM":
+                    flops = 2.0 * s.batch * s.M * s.N * s.K
+                    nbytes = 4.0 * s.batch * (s.M * s.K + s.K * s.N + s.M * s.N)
+                    mk = lambda: (rnd(s.batch, s.M, s.K), rnd(s.batch, s.K, s.N), emp(s.batch, s.M, s.N))
+                    run = lambda t: anr.gemm(t[0], t[1], t[2])
+                elif op == "TBS":
+                    flops = 2.0 * s.B * s.H * s.S * s.S * s.D
+                    nbytes = 4.0 * (2 * s.B * s.S * s.H * s.D + s.B * s.H * s.S * s.S)
+                    mk = lambda: (rnd(s.B, s.S, s.H, s.D), rnd(s.B, s.S, s.H, s.D), emp(s.B, s.H, s.S, s.S))
+                    run = lambda t: anr.tbs(t[0], t[1], t[2])
+                else:
+                    dw = op == "DEP"
+                    cin = 1 if dw else s.C
+                    flops = 2.0 * s.N * s.K * s.OH * s.OW * cin * s.R * s.S
+                    nbytes = 4.0 * (s.N * s.C * s.H * s.W + s.K * cin * s.R * s.S + s.N * s.K * s.OH * s.OW)
+                    if op == "ConvLayer":
+                        mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.K, s.C, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW),
+                                      rnd(s.K) * 0.5 + 1, rnd(s.K) * 0.1, rnd(s.K) * 0.1, rnd(s.K) * 0.75 + 1.25)
+                        run = lambda t: anr.conv_bn_relu(t[0], t[1], t[3], t[4], t[5], t[6], I.BN_EPS, t[2],
+                                                         s.stride, s.pad)
+                    elif dw:
+                        mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.C, 1, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
+                        run = lambda t: anr.dwconv(t[0], t[1], t[2], s.stride, s.pad)
+                    else:
+                        mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.K, s.C, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
+                        run = lambda t: anr.conv2d(t[0], t[1], t[2], s.stride, s.pad)
+                # enough buffer sets that a launch does not find its data in the 256 MB Infinity Cache
+                nsets = int(min(12, max(2, -(-320e6 // nbytes))))
+                sets = [mk() for _ in range(nsets)]
+                for t in sets:
+                    run(t)
+                torch.cuda.synchronize()
+                warm = time_graph(torch, lambda i: run(sets[0]), 2 * nsets)
+                cold = time_graph(torch, lambda i: run(sets[i % nsets]), 2 * nsets)
+                rows.append({"op": op, "shape": list(fields), "batch": batch, "us_warm": warm, "us_cold": cold,
+                             "tflops_cold": flops / cold / 1e6, "gbs_cold": nbytes / cold / 1e3,
+                             "frac_mfma_peak_cold": flops / cold / 1e6 / PEAK_MFMA_F32_TFLOPS,
+                             "frac_hbm_peak_cold": nbytes / cold / 1e3 / PEAK_HBM_GBS, "buffer_sets": nsets})
+                del sets
+    return rows
+
+
 def oracle_reference(I, host, name):
     import oracle
     c = host["TBG" if name == "TBS" else name]
@@ -203,6 +257,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--shape-list", action="store_true",
+                    help="instead of the step, time every Appendix C shape at batch 1 and 16 and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU figures are not produced",
@@ -224,6 +280,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_each_way": n, "copies": 10}))
+        return
+
+    if args.shape_list:
+        print(json.dumps({"metric": "launch time per Appendix C shape (HIP-graph timed, warm and cold buffers)",
+                          "unit": "us", "dtype": "f32", "data": "synthetic", "n_gpus": 1,
+                          "peaks": {"mfma_f32_tflops": PEAK_MFMA_F32_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
+                          "shapes": shape_list(anr, I, torch)}))
         return
 
     table = workload_table(I)

@@ -65,6 +65,40 @@ C2D_S2 = ConvShape(16, 256, 28, 28, 512, 3, 3, (2, 2), (1, 1))
 
 BN_EPS = 1e-5
 
+# Shape lists of the single-operator and subgraph benchmarks (Appendix C), each run at
+# batch 1 and 16 (Sec. 7.1).  Field order as in the appendix:
+#   C2D, ConvLayer: height, width, in_channels, out_channels, kernel, stride, padding
+#   GMM: N, M, K        DEP: height, width, channels, kernel, stride, padding
+#   TBS: sequence_length, heads, hidden_dimension (per head)
+APPENDIX_C = {
+    "C2D": [(224, 224, 3, 64, 7, 2, 3), (56, 56, 64, 64, 1, 1, 0), (14, 14, 256, 256, 3, 1, 1),
+            (7, 7, 512, 512, 3, 1, 1)],
+    "GMM": [(128, 128, 128), (512, 32, 512), (512, 512, 512), (1024, 1024, 1024)],
+    "DEP": [(112, 112, 32, 3, 1, 1), (112, 112, 64, 3, 2, 1), (14, 14, 512, 3, 2, 1),
+            (7, 7, 1024, 3, 1, 1)],
+    "ConvLayer": [(224, 224, 3, 64, 7, 2, 3), (56, 56, 64, 64, 3, 2, 1), (28, 28, 128, 256, 1, 2, 0),
+                  (7, 7, 512, 512, 3, 1, 1)],
+    "TBS": [(128, 12, 64), (128, 16, 64), (64, 12, 128), (128, 12, 128)],
+}
+BATCHES = (1, 16)
+
+
+def appendix_shape(op: str, fields, batch: int):
+    """The shape object of one Appendix C record at the given batch size."""
+    if op in ("C2D", "ConvLayer"):
+        h, w, ci, co, ks, st, pd = fields
+        return ConvShape(batch, ci, h, w, co, ks, ks, (st, st), (pd, pd))
+    if op == "DEP":
+        h, w, c, ks, st, pd = fields
+        return ConvShape(batch, c, h, w, c, ks, ks, (st, st), (pd, pd))
+    if op == "GMM":
+        n, m, k = fields
+        return GemmShape(m, n, k, batch)
+    if op == "TBS":
+        s, h, d = fields
+        return TbgShape(batch, s, h, d)
+    raise KeyError(op)
+
 CONFIG_SEEDS: Dict[str, int] = {
     "GMM": SEED_BASE + 1,
     "C2D": SEED_BASE + 2,

@@ -368,3 +368,8 @@ def test_golden_shape_list_parses(golden_dir):
         ops.setdefault(name, []).append(tuple(int(v) for v in vals))
     assert {k: len(v) for k, v in ops.items()} == {"C2D": 4, "GMM": 4, "DEP": 4, "ConvLayer": 4, "TBS": 4}
     assert (512, 512, 512) in ops["GMM"] and (128, 12, 64) in ops["TBS"]
+    # the list the benchmark walks is the same list
+    from paper_2006_06762_amd import inputs as I
+    assert ops == I.APPENDIX_C
+    s = I.appendix_shape("ConvLayer", I.APPENDIX_C["ConvLayer"][2], 16)
+    assert (s.N, s.C, s.K, s.R, s.stride, s.pad, s.OH, s.OW) == (16, 128, 256, 1, (2, 2), (0, 0), 14, 14)
