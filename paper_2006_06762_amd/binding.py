@@ -138,6 +138,27 @@ def workspace_size(op: int, desc) -> int:
     return int(n.value)
 
 
+_workspaces = {}
+
+
+def _workspace(op: int, desc, ws):
+    """(pointer, bytes) of the workspace for one call: the caller's tensor, else a buffer kept
+    per (device, stream) and grown on demand (calls on one stream run in order, so they can
+    share it; a call never synchronises)."""
+    need = workspace_size(op, desc)
+    if need == 0:
+        return None, 0
+    if ws is None:
+        key = (torch.cuda.current_device(), torch.cuda.current_stream().cuda_stream)
+        ws = _workspaces.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            _workspaces[key] = ws
+    if not ws.is_cuda or not ws.is_contiguous() or ws.numel() * ws.element_size() < need:
+        raise ValueError("workspace must be a contiguous CUDA tensor of at least %d bytes" % need)
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
 def gemm(A, B, C):
     """C = A.B.  A [M,K] / [b,M,K], B [K,N] / [b,K,N], C [M,N] / [b,M,N]; last dim contiguous."""
     if A.dim() == 2:
@@ -159,17 +180,19 @@ def _conv_strides(t):
     return None if t.is_contiguous() else tuple(t.stride())
 
 
-def conv2d(x, w, y, stride=(1, 1), pad=(0, 0)):
-    """y = conv2d(x, w); x [N,C,H,W], w [K,C,R,S] packed, y [N,K,OH,OW] (may be strided views)."""
+def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None):
+    """y = conv2d(x, w); x [N,C,H,W], w [K,C,R,S] packed, y [N,K,OH,OW] (may be strided views).
+    ws: optional workspace tensor of at least workspace_size(ANR_OP_CONV2D, desc) bytes."""
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
     d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y))
-    _check(_lib.anr_conv2d(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), None, 0, _stream()), "anr_conv2d")
+    wp, wb = _workspace(ANR_OP_CONV2D, d, ws)
+    _check(_lib.anr_conv2d(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), wp, wb, _stream()), "anr_conv2d")
     return y
 
 
-def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0)):
+def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None):
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
@@ -177,8 +200,9 @@ def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0)
         if tuple(v.shape) != (K,) or not v.is_contiguous():
             raise ValueError("batch-norm vectors must be packed [K]")
     d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y))
+    wp, wb = _workspace(ANR_OP_CONV_BN_RELU, d, ws)
     _check(_lib.anr_conv_bn_relu(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(gamma), _ptr(beta), _ptr(mean),
-                                 _ptr(var), ctypes.c_float(eps), _ptr(y), None, 0, _stream()),
+                                 _ptr(var), ctypes.c_float(eps), _ptr(y), wp, wb, _stream()),
            "anr_conv_bn_relu")
     return y
 

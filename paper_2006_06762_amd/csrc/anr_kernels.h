@@ -53,6 +53,7 @@ struct ConvArgs {
     float* y;
     int N, C, H, W, K, R, S;
     int stride_h, stride_w, pad_h, pad_w;
+    int dil_h, dil_w;
     int OH, OW;
     int64_t xs[4];   // element strides n,c,h,w (w stride is 1)
     int64_t ys[4];
@@ -62,7 +63,13 @@ struct ConvArgs {
     const float* mean;
     const float* var;
     float eps;
+    // caller's workspace (device memory, 16-byte aligned) for the split-K partial tiles
+    float* ws;
+    size_t ws_bytes;
 };
+// Workspace the convolution of `a` needs (0 for most shapes); a launch with less fails with
+// hipErrorInvalidValue before anything is enqueued.
+size_t conv2d_workspace_bytes(const ConvArgs& a);
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream);
 hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
 

@@ -6,6 +6,7 @@
 #include <cmath>
 
 #include "anr_kernels.h"
+#include "conv_internal.h"
 
 namespace {
 
@@ -84,11 +85,26 @@ anr::ConvArgs make_conv_args(const anr_conv_desc* d, const ConvGeom& g, const fl
     a.y = y;
     a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
+    a.dil_h = d->dil_h; a.dil_w = d->dil_w;
     a.OH = g.OH; a.OW = g.OW;
     for (int i = 0; i < 4; ++i) { a.xs[i] = g.xs[i]; a.ys[i] = g.ys[i]; }
     a.gamma = a.beta = a.mean = a.var = nullptr;
     a.eps = 0.f;
+    a.ws = nullptr;
+    a.ws_bytes = 0;
     return a;
+}
+
+// Attaches the caller's workspace; fails when the convolution needs more than it holds.
+anr_status attach_workspace(anr::ConvArgs* a, void* ws, size_t ws_bytes)
+{
+    const size_t need = anr::conv2d_workspace_bytes(*a);
+    if (need == 0) return ANR_OK;
+    if (!ws || ws_bytes < need) return ANR_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) & 15) return ANR_ERR_INVALID_ARG;
+    a->ws = static_cast<float*>(ws);
+    a->ws_bytes = ws_bytes;
+    return ANR_OK;
 }
 
 anr_status check_gemm(const anr_gemm_desc* d)
@@ -184,12 +200,13 @@ anr_status anr_gemm(const anr_gemm_desc* d, const float* A, const float* B, floa
 anr_status anr_conv2d(const anr_conv_desc* d, const float* x, const float* w, float* y, void* ws,
                       size_t ws_bytes, void* hip_stream)
 {
-    (void)ws; (void)ws_bytes;
     ConvGeom g;
     anr_status st = check_conv(d, false, &g);
     if (st != ANR_OK) return st;
     if (!x || !w || !y) return ANR_ERR_NULL;
-    const anr::ConvArgs a = make_conv_args(d, g, x, w, y);
+    anr::ConvArgs a = make_conv_args(d, g, x, w, y);
+    st = attach_workspace(&a, ws, ws_bytes);
+    if (st != ANR_OK) return st;
     return launch_status(anr::launch_conv2d(a, static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -197,7 +214,6 @@ anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float*
                             const float* beta, const float* mean, const float* var, float eps, float* y,
                             void* ws, size_t ws_bytes, void* hip_stream)
 {
-    (void)ws; (void)ws_bytes;
     ConvGeom g;
     anr_status st = check_conv(d, false, &g);
     if (st != ANR_OK) return st;
@@ -205,6 +221,8 @@ anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float*
     if (!x || !w || !y || !gamma || !beta || !mean || !var) return ANR_ERR_NULL;
     anr::ConvArgs a = make_conv_args(d, g, x, w, y);
     a.gamma = gamma; a.beta = beta; a.mean = mean; a.var = var; a.eps = eps;
+    st = attach_workspace(&a, ws, ws_bytes);
+    if (st != ANR_OK) return st;
     return launch_status(anr::launch_conv2d(a, static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -251,6 +269,12 @@ anr_status anr_workspace_size(int op, const void* desc, size_t* bytes)
     }
     if (st != ANR_OK) return st;
     *bytes = 0;
+    if (op == ANR_OP_CONV2D || op == ANR_OP_CONV_BN_RELU) {
+        // an upper bound that does not depend on pointer alignment: what the general kernel's
+        // split-K needs for this shape (the tuned kernel, when it takes the call, needs none)
+        const anr::ConvArgs a = make_conv_args(static_cast<const anr_conv_desc*>(desc), cg, nullptr, nullptr, nullptr);
+        *bytes = anr::conv2d_gather_workspace_bytes(a);
+    }
     return ANR_OK;
 }
 

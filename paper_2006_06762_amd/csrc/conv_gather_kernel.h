@@ -1,0 +1,256 @@
+// C2D and the ConvLayer subgraph (Sec. 7.1, Sec. 7.2 and Appendix C of arXiv 2006.06762)
+// for every geometry: any kernel size, stride, padding, dilation, channel count and image
+// width, any strided NCHW view.  The shape lists of the paper hold layers the tuned
+// patch-staging kernel cannot take (7x7 stride-2 stem with 3 channels, 14x14 and 7x7 maps,
+// 1x1 stride 2) and run every shape at batch 1, where one image has too few pixels to fill
+// the chip.
+//
+// Implicit GEMM with an explicit gather: rows m = output pixels (n, oh, ow), columns =
+// output channels, reduction index k = (c, r, s) in the order of the OIHW weights.  A
+// work-group owns BM pixels x BN channels and a range of reduction chunks of KC = 32.
+//   A tile  [BM][KC]: thread t gathers pixel t % BM; the k it fetches is uniform over the
+//           wave, so the split of k into (c, r, s) and the offset of that tap are scalar
+//           work, and the lane adds its pixel's base offset and tests its own bounds.
+//           Taps that fall outside the image get a buffer offset beyond the descriptor's
+//           extent: the load returns zero without a branch.  Lanes are consecutive pixels,
+//           so for stride 1 a load covers whole cache lines.
+//   B tile  [BN][KC]: rows of the weight matrix [K][C*R*S] are contiguous in k: 16-byte
+//           loads when C*R*S is a multiple of 4, single floats otherwise.
+// Both tiles sit in LDS row-major in k with a row stride of KC + 2 floats (operand reads of
+// 32 consecutive rows hit 32 different banks), double buffered, one barrier per chunk.  The
+// MFMA is v_mfma_f32_32x32x2_f32; a lane reads two k values at a time (8-byte LDS reads)
+// and feeds them to two consecutive MFMAs: half-wave h takes k = 4j + 2h and 4j + 2h + 1,
+// which is a valid reduction order because A and B use the same one.
+//
+// Split-K: with few output tiles (batch 1, 7x7 maps) the reduction chunks of a tile are dealt
+// to `ksplit` work-groups, which write partial tiles to a workspace; a second kernel sums them
+// in fixed order (deterministic, no float atomics) and runs the epilogue.
+#pragma once
+#include "anr_device.h"
+#include "conv_internal.h"
+
+namespace anr {
+namespace gconv {
+
+constexpr int KC = 32;           // reduction elements per chunk
+constexpr int WS = KC + 2;       // LDS row stride, floats
+constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset beyond any descriptor extent used here
+
+struct Plan {
+    int Mtot, ohow, Ktot, RS;
+    int tiles_m, tiles_n, ksplit, nchunks, chunks_per_split;
+    int Mpad, Kpad;              // tile-padded extents of the workspace
+    int w_vec;                   // weight rows allow 16-byte loads
+    int vec_store;               // 4 consecutive pixels of a lane are 16 contiguous, aligned bytes of y
+    uint32_t x_bytes, w_bytes;
+    FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles;
+    int bm, bn;                  // chosen tile (host side)
+};
+
+// Epilogue of one accumulator quad: registers 4q .. 4q+3 of a lane are pixels mq .. mq+3 of
+// output channel co.
+__device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v)
+{
+    if (p.gamma) {
+        const float scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
+        const float shift = p.beta[co] - p.mean[co] * scale;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fmaxf(fmaf(v[r], scale, shift), 0.f);
+    }
+    if (g.vec_store) {
+        if (mq < g.Mtot) {
+            const int n = g.d_ohow.div(mq), pix = mq - n * g.ohow;
+            stg4(p.y + n * p.ys[0] + co * p.ys[1] + pix, v);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int m = mq + r;
+            if (m < g.Mtot) {
+                const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+                const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+                p.y[n * p.ys[0] + co * p.ys[1] + oh * p.ys[2] + ow] = v[r];
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, const Plan g)
+{
+    constexpr int MB = BM / 64, NB = BN / 64;       // 32x32 blocks per wave (waves are 2 x 2)
+    constexpr int KG = 256 / BM;                    // threads per pixel in the A gather
+    constexpr int AU = KC / KG;                     // A elements per thread and chunk
+    constexpr int BU4 = BN / 32;                    // B 16-byte units per thread and chunk
+    constexpr int BU1 = BN / 8;                     // B single floats per thread and chunk
+    constexpr int A_SZ = BM * WS, B_SZ = BN * WS;   // floats per buffer
+
+    extern __shared__ __attribute__((aligned(16))) float glds[];   // A[2][BM][WS], then B[2][BN][WS]
+    float* const lds_a = glds;
+    float* const lds_b = glds + 2 * A_SZ;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // blockIdx.x = (split * tiles_n + tile_n) * tiles_m + tile_m
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int split = g.d_tiles.div((int)blockIdx.x);
+    const int trem = (int)blockIdx.x - split * tiles;
+    const int tile_n = g.d_tiles_m.div(trem), tile_m = trem - tile_n * g.tiles_m;
+    const int m0 = tile_m * BM, co0 = tile_n * BN;
+    const int c_begin = split * g.chunks_per_split;
+    const int c_end = c_begin + g.chunks_per_split < g.nchunks ? c_begin + g.chunks_per_split : g.nchunks;
+
+    // ---- the pixel this thread gathers for
+    const int am = tid % BM;
+    const int akg = __builtin_amdgcn_readfirstlane(tid / BM);    // uniform over the wave
+    int m = m0 + am;
+    m = m < g.Mtot ? m : g.Mtot - 1;          // rows past the end repeat the last pixel, never stored
+    int ihb, iwb, xbase;
+    {
+        const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+        const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+        ihb = oh * p.stride_h - p.pad_h;
+        iwb = ow * p.stride_w - p.pad_w;
+        xbase = (int)(n * p.xs[0] + ihb * p.xs[2] + iwb);         // may be negative; valid taps make it >= 0
+    }
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
+
+    float ra[AU];
+    f32x4 rb4[BU4];
+    float rb1[BU1];
+
+    auto load_chunk = [&](int chunk) {
+        const int k0 = chunk * KC;
+#pragma unroll
+        for (int j = 0; j < AU; ++j) {
+            const int k = k0 + akg + KG * j;                       // scalar
+            const int c = g.d_rs.div(k), tap = k - c * g.RS;
+            const int r = g.d_s.div(tap), s = tap - r * p.S;
+            const int dr = k < g.Ktot ? r * p.dil_h : (1 << 28);   // k past the end: no lane is in bounds
+            const int ds = s * p.dil_w;
+            const int koff = (int)(c * p.xs[1] + dr * p.xs[2] + ds);
+            const bool ok = (unsigned)(ihb + dr) < (unsigned)p.H && (unsigned)(iwb + ds) < (unsigned)p.W;
+            const uint32_t off = ok ? 4u * (uint32_t)(xbase + koff) : kOutOfRange;
+            ra[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
+        }
+        if (g.w_vec) {
+#pragma unroll
+            for (int j = 0; j < BU4; ++j) {
+                const int col = (tid >> 3) + 32 * j, k = k0 + 4 * (tid & 7);
+                int co = co0 + col;
+                co = co < p.K ? co : p.K - 1;                     // columns past K repeat the last, never stored
+                const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
+                rb4[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < BU1; ++j) {
+                const int col = (tid >> 5) + 8 * j, k = k0 + (tid & 31);
+                int co = co0 + col;
+                co = co < p.K ? co : p.K - 1;
+                const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
+                rb1[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, (int)off, 0, 0));
+            }
+        }
+    };
+    auto store_chunk = [&](int buf) {
+        float* const a = lds_a + buf * A_SZ;
+        float* const b = lds_b + buf * B_SZ;
+#pragma unroll
+        for (int j = 0; j < AU; ++j) a[am * WS + akg + KG * j] = ra[j];
+        if (g.w_vec) {
+#pragma unroll
+            for (int j = 0; j < BU4; ++j) {
+                f32x2* dst = reinterpret_cast<f32x2*>(&b[((tid >> 3) + 32 * j) * WS + 4 * (tid & 7)]);
+                const f32x2 lo = {rb4[j][0], rb4[j][1]}, hi = {rb4[j][2], rb4[j][3]};
+                dst[0] = lo;
+                dst[1] = hi;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < BU1; ++j) b[((tid >> 5) + 8 * j) * WS + (tid & 31)] = rb1[j];
+        }
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    load_chunk(c_begin);
+    store_chunk(0);
+    __syncthreads();
+    for (int c = c_begin; c < c_end; ++c) {
+        const int buf = (c - c_begin) & 1;
+        // the chunk after the last is the last again: loaded and stored, never read (no branch
+        // around the loads)
+        load_chunk(c + 1 < c_end ? c + 1 : c);
+        const float* a = lds_a + buf * A_SZ + (wm * MB * 32 + r32) * WS + 2 * h;
+        const float* b = lds_b + buf * B_SZ + (wn * NB * 32 + r32) * WS + 2 * h;
+#pragma unroll
+        for (int j = 0; j < KC / 4; ++j) {
+            f32x2 av[MB], bv[NB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WS + 4 * j);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WS + 4 * j);
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
+        }
+        store_chunk(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- accumulator register r of lane (h, r32): pixel 8*(r/4) + 4*h + r%4, channel r32 of the block
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int col = co0 + (wn * NB + nb) * 32 + r32;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int mq = m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h;
+                const f32x4 v = {acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
+                                 acc[mb][nb][4 * q + 3]};
+                if (g.ksplit > 1) {
+                    // the workspace is padded to whole tiles: no bounds to test
+                    stg4(p.ws + ((int64_t)split * g.Kpad + col) * g.Mpad + mq, v);
+                } else if (col < p.K) {
+                    store_quad(p, g, mq, col, v);
+                }
+            }
+        }
+}
+
+// Sums the ksplit partial tiles in split order and runs the epilogue: one thread per
+// (output channel, four consecutive pixels).
+__global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs p, const Plan g)
+{
+    const int mquads = g.Mpad >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int co = (int)(idx / mquads), mq = 4 * (int)(idx - (int64_t)co * mquads);
+    if (co >= p.K || mq >= g.Mtot) return;
+    f32x4 v = zero4();
+    for (int s = 0; s < g.ksplit; ++s) {
+        const f32x4 t = ldg4(p.ws + ((int64_t)s * g.Kpad + co) * g.Mpad + mq);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] += t[r];
+    }
+    store_quad(p, g, mq, co, v);
+}
+
+}  // namespace gconv
+}  // namespace anr

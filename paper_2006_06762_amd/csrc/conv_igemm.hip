@@ -43,37 +43,52 @@ bool try_fixed(const ConvArgs& a, const Geom& g, size_t lds, hipStream_t stream,
     return true;
 }
 
-}  // namespace
 
-hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken)
+// Picks the variant for `a`: its index, geometry and LDS size; -1 when no variant runs it.
+int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
 {
-    *taken = false;
     const int64_t x_extent = (int64_t)(a.N - 1) * a.xs[0] + (int64_t)(a.C - 1) * a.xs[1] +
                              (int64_t)(a.H - 1) * a.xs[2] + a.W;
     const int64_t w_extent = (int64_t)a.K * a.C * a.R * a.S;
     // 32-bit byte offsets inside x and w, 31-bit pixel and virtual-row indices
     const bool k3 = a.R == 3 && a.S == 3 && (a.C % 8 == 0);
     const bool k1 = a.R == 1 && a.S == 1 && (a.C % 32 == 0);
-    const bool ok = (k3 || k1) && (a.W % 4 == 0) && is_aligned16(a.x) &&
+    const bool ok = (k3 || k1) && a.dil_h == 1 && a.dil_w == 1 && (a.W % 4 == 0) && is_aligned16(a.x) &&
                     is_aligned16(a.w) && (a.xs[0] % 4 == 0) && (a.xs[1] % 4 == 0) &&
                     (a.xs[2] % 4 == 0) && x_extent < (int64_t)1 << 30 && w_extent < (int64_t)1 << 30 &&
                     (int64_t)a.N * a.OH * a.OW < (int64_t)1 << 30;
-    if (!ok) return hipSuccess;
+    if (!ok) return -1;
 
     double best_cost = 0.0;
     int best = -1;
+    if (k3) {
+        consider<V224x64>(a, &best_cost, &best, 0, g, lds);
+        consider<V224x32>(a, &best_cost, &best, 1, g, lds);
+        consider<V128x64>(a, &best_cost, &best, 2, g, lds);
+        consider<V64x64>(a, &best_cost, &best, 3, g, lds);
+    } else {
+        consider<P224x64>(a, &best_cost, &best, 4, g, lds);
+        consider<P224x32>(a, &best_cost, &best, 5, g, lds);
+        consider<P64x64>(a, &best_cost, &best, 6, g, lds);
+    }
+    return best;
+}
+
+}  // namespace
+
+bool conv2d_igemm_takes(const ConvArgs& a)
+{
     Geom g;
     size_t lds = 0;
-    if (k3) {
-        consider<V224x64>(a, &best_cost, &best, 0, &g, &lds);
-        consider<V224x32>(a, &best_cost, &best, 1, &g, &lds);
-        consider<V128x64>(a, &best_cost, &best, 2, &g, &lds);
-        consider<V64x64>(a, &best_cost, &best, 3, &g, &lds);
-    } else {
-        consider<P224x64>(a, &best_cost, &best, 4, &g, &lds);
-        consider<P224x32>(a, &best_cost, &best, 5, &g, &lds);
-        consider<P64x64>(a, &best_cost, &best, 6, &g, &lds);
-    }
+    return select_variant(a, &g, &lds) >= 0;
+}
+
+hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken)
+{
+    *taken = false;
+    Geom g;
+    size_t lds = 0;
+    const int best = select_variant(a, &g, &lds);
     if (best < 0) return hipSuccess;
     *taken = true;
     hipError_t err = hipSuccess;
@@ -93,10 +108,17 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
     }
 }
 
+size_t conv2d_workspace_bytes(const ConvArgs& a)
+{
+    return conv2d_igemm_takes(a) ? 0 : conv2d_gather_workspace_bytes(a);
+}
+
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream)
 {
     bool taken = false;
     hipError_t err = launch_conv2d_igemm(a, stream, &taken);
+    if (taken || err != hipSuccess) return err;
+    err = launch_conv2d_gather(a, stream, &taken);
     if (taken || err != hipSuccess) return err;
     return launch_conv2d_direct(a, stream);
 }

@@ -57,27 +57,6 @@
 namespace anr {
 namespace igemm {
 
-// floor(n / d) for 0 <= n < 2^31 as one multiply-high and one shift (Granlund-Montgomery
-// round-up method: mul = ceil(2^(31+l) / d), l = ceil(log2 d), quotient = (n*mul) >> (31+l)).
-struct FastDiv {
-    uint32_t mul, shr;
-    __device__ __forceinline__ int div(int n) const
-    {
-        return mul ? (int)(__umulhi((uint32_t)n, mul) >> shr) : n;
-    }
-};
-
-inline FastDiv make_fastdiv(int d)
-{
-    FastDiv f{0u, 0u};
-    if (d <= 1) return f;
-    int l = 0;
-    while ((1ll << l) < d) ++l;
-    f.mul = (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)d - 1) / (uint64_t)d);
-    f.shr = (uint32_t)(l - 1);
-    return f;
-}
-
 struct Geom {
     int Mtot;       // N*OH*OW
     int HV;         // virtual image height: (OH-1)*stride_h + R

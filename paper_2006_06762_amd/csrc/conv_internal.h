@@ -11,6 +11,14 @@ hipError_t launch_dwconv_direct(const ConvArgs& a, hipStream_t stream);
 // outside what the kernel supports (the caller then uses the direct kernel).
 hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken);
 
+// Whether launch_conv2d_igemm would take the problem (same selection, nothing launched).
+bool conv2d_igemm_takes(const ConvArgs& a);
+
+// General implicit-GEMM convolution with gathered operands and optional split-K over a
+// workspace.  *taken false: extents beyond its 32-bit offsets (the direct kernel runs then).
+hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken);
+size_t conv2d_gather_workspace_bytes(const ConvArgs& a);
+
 // Register-sliding 3x3 / stride 1 / pad 1 depthwise kernel; same contract.
 hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken);
 
