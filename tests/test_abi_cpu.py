@@ -163,6 +163,17 @@ def test_workspace_size():
     assert B.workspace_size(B.ANR_OP_CONV2D, c) == 0
     assert B.workspace_size(B.ANR_OP_CONV_BN_RELU, c) == 0
     assert B.workspace_size(B.ANR_OP_TBG, B.TbgDesc(16, 128, 12, 64)) == 0
+    # few output tiles and a long reduction: the general kernel splits K over a workspace
+    small = B.conv_desc((1, 512, 7, 7), 512, 3, 3, (1, 1), (1, 1))
+    need = B.workspace_size(B.ANR_OP_CONV2D, small)
+    assert need > 0 and need % 16 == 0
+    assert B.workspace_size(B.ANR_OP_CONV_BN_RELU, small) == need
+    lib = B.raw()
+    # reported before anything is launched: missing, too small, misaligned
+    assert lib.anr_conv2d(ctypes.byref(small), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_WORKSPACE
+    assert lib.anr_conv2d(ctypes.byref(small), DUMMY, DUMMY, DUMMY, DUMMY, need - 1, None) == B.ANR_ERR_WORKSPACE
+    assert lib.anr_conv2d(ctypes.byref(small), DUMMY, DUMMY, DUMMY, ctypes.c_void_p(0x1004), need,
+                          None) == B.ANR_ERR_INVALID_ARG
     with pytest.raises(B.AnrError):
         B.workspace_size(B.ANR_OP_DWCONV, c.__class__(1, 4, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 0))
     with pytest.raises(B.AnrError):

@@ -130,7 +130,7 @@ CONV_FAST = [
     I.ConvShape(2, 32, 12, 16, 16, 1, 1, (2, 2), (0, 0)),
     I.ConvShape(1, 96, 9, 8, 33, 1, 1, (1, 1), (1, 1)),
 ]
-# everything else goes through the direct kernel
+# everything else goes through the general gather kernel
 CONV_GENERIC = [
     I.ConvShape(2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1)),
     I.ConvShape(1, 3, 30, 30, 8, 7, 7, (2, 2), (3, 3)),
@@ -138,6 +138,18 @@ CONV_GENERIC = [
     I.ConvShape(2, 16, 14, 14, 12, 1, 1, (2, 2), (0, 0)),
     I.ConvShape(1, 12, 7, 7, 9, 3, 3, (1, 1), (1, 1)),
     I.ConvShape(1, 2, 6, 8, 2, 3, 2, (2, 1), (0, 1)),
+    # several pixel tiles and a ragged last one, reduction length not a multiple of 4 or 32
+    I.ConvShape(3, 5, 15, 13, 70, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 3, 37, 41, 64, 7, 7, (2, 2), (3, 3)),
+    I.ConvShape(1, 7, 9, 9, 130, 5, 5, (1, 1), (2, 2)),
+    # few output tiles, long reduction: split-K through the workspace
+    I.ConvShape(1, 256, 14, 14, 64, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(1, 512, 7, 7, 96, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 128, 14, 14, 80, 1, 1, (2, 2), (0, 0)),
+    I.ConvShape(1, 101, 5, 6, 33, 3, 3, (1, 1), (1, 1)),
+    # more output channels than pixels, kernel larger than the padded image allows in places
+    I.ConvShape(1, 16, 3, 3, 200, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(4, 6, 8, 5, 10, 4, 2, (3, 2), (2, 1)),
 ]
 
 
@@ -149,6 +161,58 @@ def test_conv2d_small(anr, shape, ints):
     anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad)
     check_guard(buf)
     assert_parity(y, oracle.conv2d(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
+
+
+def test_conv2d_split_k_workspace(anr):
+    """A split-K shape with the caller's own workspace, twice: the partial tiles are summed in
+    a fixed order, so both runs agree bit for bit; too small a workspace is an error."""
+    from paper_2006_06762_amd import binding as B
+    s = I.ConvShape(1, 512, 7, 7, 512, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 210)
+    d = B.conv_desc((s.N, s.C, s.H, s.W), s.K, s.R, s.S, s.stride, s.pad)
+    need = B.workspace_size(B.ANR_OP_CONV2D, d)
+    assert need > 0
+    ws = torch.full((need + 256,), 0x7f, dtype=torch.uint8, device="cuda")    # NaN-ish garbage
+    xd, wd = dev(x), dev(w)
+    y1 = torch.empty((1, s.K, s.OH, s.OW), device="cuda")
+    y2 = torch.empty_like(y1)
+    anr.conv2d(xd, wd, y1, s.stride, s.pad, ws=ws)
+    anr.conv2d(xd, wd, y2, s.stride, s.pad)             # the binding's own workspace
+    assert_parity(y1, oracle.conv2d(x, w, s.stride, s.pad), what="split-K conv")
+    assert torch.equal(y1, y2)
+    assert bool((ws[need:] == 0x7f).all()), "wrote past the stated workspace size"
+    with pytest.raises(ValueError):
+        anr.conv2d(xd, wd, y2, s.stride, s.pad, ws=ws[:need // 2])
+    st = B.raw().anr_conv2d(__import__("ctypes").byref(d), B._ptr(xd), B._ptr(wd), B._ptr(y2), None, 0,
+                            B._stream())
+    assert st == B.ANR_ERR_WORKSPACE
+
+
+def test_conv_bn_relu_split_k(anr):
+    """The fused epilogue runs in the reduce kernel when the reduction is split."""
+    s = I.ConvShape(1, 256, 14, 14, 256, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 211)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 212)
+    buf, y = guarded((1, s.K, s.OH, s.OW))
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+    assert_parity(y, ref, what="split-K ConvLayer")
+    assert float(y.min()) >= 0.0
+
+
+def test_conv2d_gather_strided_views(anr):
+    """Odd-width, unaligned views (one float into a wider buffer) take the general kernel."""
+    s = I.ConvShape(2, 6, 9, 7, 10, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 213)
+    xw = torch.zeros((2, 8, 11, 10), device="cuda")
+    xw[:, 1:7, 1:10, 1:8] = dev(x)
+    yw = torch.full((2, 12, s.OH + 1, s.OW + 3), CANARY, device="cuda")
+    yv = yw[:, 1:11, :s.OH, 2:2 + s.OW]
+    anr.conv2d(xw[:, 1:7, 1:10, 1:8], dev(w), yv, s.stride, s.pad)
+    assert_parity(yv.contiguous(), oracle.conv2d(x, w, s.stride, s.pad), what="gather strided views")
+    yw[:, 1:11, :s.OH, 2:2 + s.OW] = CANARY
+    assert bool((yw == CANARY).all()), "store outside the output view"
 
 
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
