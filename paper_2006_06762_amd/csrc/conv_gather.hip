@@ -9,10 +9,14 @@ using namespace gconv;
 
 struct Tile {
     int bm, bn;
-    double eff;     // MFMA issue efficiency relative to the largest tile (fewer loads per MFMA)
+    double chunk_us;    // time of one chunk of one work-group when the matrix pipes are the limit
+    int occupancy;      // work-groups one CU holds (LDS)
 };
-constexpr Tile kTiles[] = {{128, 128, 1.0}, {128, 64, 0.8}, {64, 64, 0.6}};
+constexpr Tile kTiles[] = {{128, 128, 3.3, 2}, {128, 64, 2.0, 3}, {64, 64, 1.2, 4}};
 constexpr int kCUs = 256;
+constexpr double kLaunchUs = 2.0;            // launch plus prologue and epilogue
+constexpr double kChunkLatencyUs = 1.5;      // one dependent global-memory round trip under load
+constexpr double kWsBytesPerUs = 3.0e6;      // workspace traffic, bytes per microsecond
 
 bool make_plan(const ConvArgs& a, Plan* g)
 {
@@ -22,6 +26,11 @@ bool make_plan(const ConvArgs& a, Plan* g)
     const int64_t Mtot = (int64_t)a.N * a.OH * a.OW;
     // byte offsets must stay below the out-of-range marker of the buffer loads (2^31)
     if (x_extent >= ((int64_t)1 << 29) || w_extent >= ((int64_t)1 << 29) || Mtot >= ((int64_t)1 << 30))
+        return false;
+    // the tap table packs row and column displacements into 16 bits each, and a displacement
+    // of kNoRow must leave every image
+    if (a.H + a.pad_h >= kMaxExtent || a.W + a.pad_w >= kMaxExtent || (a.R - 1) * (int64_t)a.dil_h >= kMaxExtent ||
+        (a.S - 1) * (int64_t)a.dil_w >= kMaxExtent)
         return false;
     g->Mtot = (int)Mtot;
     g->ohow = a.OH * a.OW;
@@ -39,41 +48,76 @@ bool make_plan(const ConvArgs& a, Plan* g)
     g->d_s = make_fastdiv(a.S);
     g->d_ohow = make_fastdiv(g->ohow);
 
-    // tile and split: fewest rounds of work-groups over the CUs, weighted by the tile's efficiency
+    return true;
+}
+
+// Fixes the tile and the split of the reduction (ks is lowered until no split is empty).
+void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
+{
+    g->bm = bm;
+    g->bn = bn;
+    g->tiles_m = (g->Mtot + bm - 1) / bm;
+    g->tiles_n = (a.K + bn - 1) / bn;
+    if (ks > g->nchunks) ks = g->nchunks;
+    g->chunks_per_split = (g->nchunks + ks - 1) / ks;
+    g->ksplit = (g->nchunks + g->chunks_per_split - 1) / g->chunks_per_split;
+    g->Mpad = g->tiles_m * bm;
+    g->Kpad = g->tiles_n * bn;
+    g->d_tiles_m = make_fastdiv(g->tiles_m);
+    g->d_tiles = make_fastdiv(g->tiles_m * g->tiles_n);
+}
+
+// Estimated run time in microseconds of tile t with the reduction split ks ways.  Two bounds:
+// the MFMA work of the busiest CU (work-groups are dealt evenly over the CUs and those on one
+// CU share its matrix pipes), and the chain of dependent memory round trips of one work-group
+// (one per chunk, with one chunk of look-ahead), which concurrency hides only across
+// work-groups.  Constants are fits to measurements on the shape lists of Appendix C.
+double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
+{
+    const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * ((a.K + t.bn - 1) / t.bn);
+    const int cps = (g.nchunks + ks - 1) / ks;
+    const int ks_eff = (g.nchunks + cps - 1) / cps;
+    const int64_t wgs = tiles * ks_eff;
+    const double per_cu = (double)((wgs + kCUs - 1) / kCUs);
+    const double mfma_us = per_cu * cps * t.chunk_us;
+    const double resident = per_cu < t.occupancy ? per_cu : t.occupancy;
+    const double latency_us = (per_cu / resident) * (cps + 1) * kChunkLatencyUs;
+    double us = kLaunchUs + (mfma_us > latency_us ? mfma_us : latency_us);
+    if (ks_eff > 1) {
+        // second launch; partial tiles written and read back
+        const double ws_bytes = 4.0 * ks_eff * tiles * t.bm * t.bn;
+        us += kLaunchUs + 2.0 * ws_bytes / kWsBytesPerUs;
+    }
+    return us;
+}
+
+bool choose_tile(const ConvArgs& a, Plan* g)
+{
     double best = 0.0;
     bool have = false;
+    int bm = 0, bn = 0, bks = 1;
     for (const Tile& t : kTiles) {
-        const int64_t tm = (Mtot + t.bm - 1) / t.bm, tn = (a.K + t.bn - 1) / t.bn;
-        const int64_t tiles = tm * tn;
+        const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * ((a.K + t.bn - 1) / t.bn);
         if (tiles >= ((int64_t)1 << 24)) continue;
-        int ks = 1;
-        if (tiles < 192) {
-            const int want = (int)((320 + tiles - 1) / tiles);          // aim at ~320 work-groups
-            const int most = g->nchunks / 2 > 1 ? g->nchunks / 2 : 1;     // at least two chunks per split
-            ks = want < most ? want : most;
-        }
-        const int cps = (g->nchunks + ks - 1) / ks;
-        ks = (g->nchunks + cps - 1) / cps;                               // no empty split
-        const int64_t wgs = tiles * ks;
-        const double rounds = (double)((wgs + kCUs - 1) / kCUs);
-        double cost = rounds * cps * (double)t.bm * t.bn / t.eff;
-        if (ks > 1) cost += 3.0 * 128 * 128;                             // second launch and the partial tiles
-        if (!have || cost < best) {
-            have = true;
-            best = cost;
-            g->bm = t.bm;
-            g->bn = t.bn;
-            g->tiles_m = (int)tm;
-            g->tiles_n = (int)tn;
-            g->ksplit = ks;
-            g->chunks_per_split = cps;
+        const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;      // enough tiles: no split
+        int last_cps = 0;
+        for (int ks = 1; ks <= most; ++ks) {
+            const int cps = (g->nchunks + ks - 1) / ks;
+            if (cps == last_cps) continue;                        // same split as the previous ks
+            last_cps = cps;
+            if (4.0 * ks * tiles * t.bm * t.bn > 256e6) break;     // keep the workspace modest
+            const double us = estimate_us(*g, a, t, ks);
+            if (!have || us < best) {
+                have = true;
+                best = us;
+                bm = t.bm;
+                bn = t.bn;
+                bks = ks;
+            }
         }
     }
     if (!have) return false;
-    g->Mpad = g->tiles_m * g->bm;
-    g->Kpad = g->tiles_n * g->bn;
-    g->d_tiles_m = make_fastdiv(g->tiles_m);
-    g->d_tiles = make_fastdiv(g->tiles_m * g->tiles_n);
+    set_tile(a, g, bm, bn, bks);
     return true;
 }
 
@@ -98,17 +142,24 @@ hipError_t launch_tile(const ConvArgs& a, const Plan& g, hipStream_t stream)
 
 }  // namespace
 
+hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stream);
+
 size_t conv2d_gather_workspace_bytes(const ConvArgs& a)
 {
     Plan g;
-    return make_plan(a, &g) ? plan_workspace(g) : 0;
+    return make_plan(a, &g) && choose_tile(a, &g) ? plan_workspace(g) : 0;
 }
 
 hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
     Plan g;
-    *taken = make_plan(a, &g);
+    *taken = make_plan(a, &g) && choose_tile(a, &g);
     if (!*taken) return hipSuccess;
+    return launch_gather_plan(a, g, stream);
+}
+
+hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stream)
+{
     const size_t need = plan_workspace(g);
     if (need > 0 && (a.ws == nullptr || a.ws_bytes < need || !is_aligned16(a.ws))) return hipErrorInvalidValue;
     hipError_t err;

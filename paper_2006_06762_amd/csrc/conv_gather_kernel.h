@@ -26,6 +26,8 @@
 // to `ksplit` work-groups, which write partial tiles to a workspace; a second kernel sums them
 // in fixed order (deterministic, no float atomics) and runs the epilogue.
 #pragma once
+#include <type_traits>
+
 #include "anr_device.h"
 #include "conv_internal.h"
 
@@ -35,6 +37,8 @@ namespace gconv {
 constexpr int KC = 32;           // reduction elements per chunk
 constexpr int WS = KC + 2;       // LDS row stride, floats
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset beyond any descriptor extent used here
+constexpr int kNoRow = 0x7fff;                  // row displacement of a reduction index past the end
+constexpr int kMaxExtent = 16000;               // image height/width and kernel extents the tap table packs
 
 struct Plan {
     int Mtot, ohow, Ktot, RS;
@@ -81,11 +85,14 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
     constexpr int MB = BM / 64, NB = BN / 64;       // 32x32 blocks per wave (waves are 2 x 2)
     constexpr int KG = 256 / BM;                    // threads per pixel in the A gather
     constexpr int AU = KC / KG;                     // A elements per thread and chunk
+    static_assert(AU % 8 == 0, "gather loads are issued in groups of eight");
     constexpr int BU4 = BN / 32;                    // B 16-byte units per thread and chunk
     constexpr int BU1 = BN / 8;                     // B single floats per thread and chunk
     constexpr int A_SZ = BM * WS, B_SZ = BN * WS;   // floats per buffer
 
+    typedef int i32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __attribute__((aligned(16))) float glds[];   // A[2][BM][WS], then B[2][BN][WS]
+    __shared__ i32x2 ktab[2 * KC];                                 // tap tables of two chunks
     float* const lds_a = glds;
     float* const lds_b = glds + 2 * A_SZ;
 
@@ -121,23 +128,45 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
     const __amdgpu_buffer_rsrc_t wrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
 
-    float ra[AU];
-    f32x4 rb4[BU4];
-    float rb1[BU1];
+    // Two chunks of look-ahead in registers: while chunk c is multiplied out of LDS, chunk c+1
+    // waits in one register set and the loads of chunk c+2 go out into the other, so a load has
+    // two chunks of MFMA time to come back.
+    float ra[2][AU];
+    float rb[2][BU1];                     // BU4 16-byte units or BU1 single floats: the same registers
 
-    auto load_chunk = [&](int chunk) {
-        const int k0 = chunk * KC;
-#pragma unroll
-        for (int j = 0; j < AU; ++j) {
-            const int k = k0 + akg + KG * j;                       // scalar
+    // The tap table of one chunk: for each of its KC reduction indices the offset of the tap
+    // (c, r, s) inside an image and its row and column displacement.  32 threads fill it a chunk
+    // ahead, so a gather load costs one broadcast LDS read instead of two scalar divisions.
+    auto fill_taps = [&](int chunk, int slot) {
+        if (tid < KC) {
+            const int k = chunk * KC + tid;
             const int c = g.d_rs.div(k), tap = k - c * g.RS;
             const int r = g.d_s.div(tap), s = tap - r * p.S;
-            const int dr = k < g.Ktot ? r * p.dil_h : (1 << 28);   // k past the end: no lane is in bounds
-            const int ds = s * p.dil_w;
-            const int koff = (int)(c * p.xs[1] + dr * p.xs[2] + ds);
-            const bool ok = (unsigned)(ihb + dr) < (unsigned)p.H && (unsigned)(iwb + ds) < (unsigned)p.W;
-            const uint32_t off = ok ? 4u * (uint32_t)(xbase + koff) : kOutOfRange;
-            ra[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
+            // offset of the tap, then row and column displacement packed as two 16-bit fields; a k
+            // past the end gets a row displacement no pixel can be in bounds with
+            const int dr = k < g.Ktot ? r * p.dil_h : kNoRow;
+            i32x2 e;
+            e[0] = (int)(c * p.xs[1] + (r * p.dil_h) * p.xs[2] + s * p.dil_w);
+            e[1] = (dr << 16) | (s * p.dil_w);
+            ktab[slot * KC + tid] = e;
+        }
+    };
+    auto load_chunk = [&](int chunk, int slot, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        const int k0 = chunk * KC;
+#pragma unroll
+        for (int j0 = 0; j0 < AU; j0 += 8) {
+            // the table reads of eight loads go out together: one LDS round trip, not eight
+            i32x2 e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = ktab[slot * KC + akg + KG * (j0 + j)];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int dr = e[j][1] >> 16, ds = e[j][1] & 0xffff;
+                const bool ok = ((unsigned)(ihb + dr) < (unsigned)p.H) & ((unsigned)(iwb + ds) < (unsigned)p.W);
+                const uint32_t off = ok ? 4u * (uint32_t)(xbase + e[j][0]) : kOutOfRange;
+                ra[set][j0 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
+            }
         }
         if (g.w_vec) {
 #pragma unroll
@@ -146,7 +175,9 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
                 int co = co0 + col;
                 co = co < p.K ? co : p.K - 1;                     // columns past K repeat the last, never stored
                 const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
-                rb4[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0));
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rb[set][4 * j + i] = v[i];
             }
         } else {
 #pragma unroll
@@ -155,26 +186,27 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
                 int co = co0 + col;
                 co = co < p.K ? co : p.K - 1;
                 const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
-                rb1[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, (int)off, 0, 0));
+                rb[set][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, (int)off, 0, 0));
             }
         }
     };
-    auto store_chunk = [&](int buf) {
+    auto store_chunk = [&](int buf, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
         float* const a = lds_a + buf * A_SZ;
         float* const b = lds_b + buf * B_SZ;
 #pragma unroll
-        for (int j = 0; j < AU; ++j) a[am * WS + akg + KG * j] = ra[j];
+        for (int j = 0; j < AU; ++j) a[am * WS + akg + KG * j] = ra[set][j];
         if (g.w_vec) {
 #pragma unroll
             for (int j = 0; j < BU4; ++j) {
                 f32x2* dst = reinterpret_cast<f32x2*>(&b[((tid >> 3) + 32 * j) * WS + 4 * (tid & 7)]);
-                const f32x2 lo = {rb4[j][0], rb4[j][1]}, hi = {rb4[j][2], rb4[j][3]};
+                const f32x2 lo = {rb[set][4 * j], rb[set][4 * j + 1]}, hi = {rb[set][4 * j + 2], rb[set][4 * j + 3]};
                 dst[0] = lo;
                 dst[1] = hi;
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < BU1; ++j) b[((tid >> 5) + 8 * j) * WS + (tid & 31)] = rb1[j];
+            for (int j = 0; j < BU1; ++j) b[((tid >> 5) + 8 * j) * WS + (tid & 31)] = rb[set][j];
         }
     };
 
@@ -186,16 +218,31 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
-    load_chunk(c_begin);
-    store_chunk(0);
+    // chunks past the end of the range are the last chunk again: loaded, never multiplied (no
+    // branch around the loads)
+    auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+
+    fill_taps(c_begin, 0);
+    fill_taps(clampc(c_begin + 1), 1);
     __syncthreads();
-    for (int c = c_begin; c < c_end; ++c) {
-        const int buf = (c - c_begin) & 1;
-        // the chunk after the last is the last again: loaded and stored, never read (no branch
-        // around the loads)
-        load_chunk(c + 1 < c_end ? c + 1 : c);
-        const float* a = lds_a + buf * A_SZ + (wm * MB * 32 + r32) * WS + 2 * h;
-        const float* b = lds_b + buf * B_SZ + (wn * NB * 32 + r32) * WS + 2 * h;
+    load_chunk(c_begin, 0, S0{});
+    load_chunk(clampc(c_begin + 1), 1, S1{});
+    __syncthreads();                       // every wave has read both tap tables
+    fill_taps(clampc(c_begin + 2), 0);
+    store_chunk(0, S0{});
+    __syncthreads();
+
+    // Iteration c: LDS buffer and tap slot of parity P hold chunk c and the taps of chunk c+2;
+    // register set P is free, set P^1 holds chunk c+1.
+    auto iteration = [&](int c, auto par_c) {
+        constexpr int P = decltype(par_c)::value;
+        load_chunk(clampc(c + 2), P, std::integral_constant<int, P>{});
+        // keep the loads ahead of the MFMAs (the scheduler would sink them to their first use)
+        __builtin_amdgcn_sched_barrier(0);
+        const float* a = lds_a + P * A_SZ + (wm * MB * 32 + r32) * WS + 2 * h;
+        const float* b = lds_b + P * B_SZ + (wn * NB * 32 + r32) * WS + 2 * h;
 #pragma unroll
         for (int j = 0; j < KC / 4; ++j) {
             f32x2 av[MB], bv[NB];
@@ -210,8 +257,14 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
         }
-        store_chunk(buf ^ 1);
+        store_chunk(P ^ 1, std::integral_constant<int, P ^ 1>{});
+        // slot P^1 held the taps of chunk c+1, last read before the previous barrier
+        fill_taps(clampc(c + 3), P ^ 1);
         __syncthreads();
+    };
+    for (int c = c_begin; c < c_end; c += 2) {
+        iteration(c, S0{});
+        if (c + 1 < c_end) iteration(c + 1, S1{});
     }
 
     // ---- accumulator register r of lane (h, r32): pixel 8*(r/4) + 4*h + r%4, channel r32 of the block
