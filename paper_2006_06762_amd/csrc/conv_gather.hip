@@ -9,13 +9,13 @@ using namespace gconv;
 
 struct Tile {
     int bm, bn;
-    double chunk_us;    // time of one chunk of one work-group when the matrix pipes are the limit
-    int occupancy;      // work-groups one CU holds (LDS)
+    double chunk_us;    // CU time per chunk and work-group when the CU is saturated with work-groups
+    double lone_us;     // time per chunk of a work-group that has its CU to itself
+    int occupancy;      // work-groups one CU holds (LDS, registers)
 };
-constexpr Tile kTiles[] = {{128, 128, 3.3, 2}, {128, 64, 2.0, 3}, {64, 64, 1.2, 4}};
+constexpr Tile kTiles[] = {{128, 128, 3.2, 2.8, 2}, {128, 64, 1.6, 1.9, 3}, {64, 64, 0.8, 1.1, 4}};
 constexpr int kCUs = 256;
 constexpr double kLaunchUs = 2.0;            // launch plus prologue and epilogue
-constexpr double kChunkLatencyUs = 1.5;      // one dependent global-memory round trip under load
 constexpr double kWsBytesPerUs = 3.0e6;      // workspace traffic, bytes per microsecond
 
 bool make_plan(const ConvArgs& a, Plan* g)
@@ -68,10 +68,10 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
 }
 
 // Estimated run time in microseconds of tile t with the reduction split ks ways.  Two bounds:
-// the MFMA work of the busiest CU (work-groups are dealt evenly over the CUs and those on one
-// CU share its matrix pipes), and the chain of dependent memory round trips of one work-group
-// (one per chunk, with one chunk of look-ahead), which concurrency hides only across
-// work-groups.  Constants are fits to measurements on the shape lists of Appendix C.
+// the work of the busiest CU when it is saturated (work-groups are dealt evenly over the CUs
+// and those on one CU share its matrix pipes), and the serial chain of chunks of one
+// work-group, which only concurrency across work-groups hides.  Constants are fits to
+// measurements on the shape lists of Appendix C.
 double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
 {
     const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * ((a.K + t.bn - 1) / t.bn);
@@ -81,7 +81,7 @@ double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
     const double per_cu = (double)((wgs + kCUs - 1) / kCUs);
     const double mfma_us = per_cu * cps * t.chunk_us;
     const double resident = per_cu < t.occupancy ? per_cu : t.occupancy;
-    const double latency_us = (per_cu / resident) * (cps + 1) * kChunkLatencyUs;
+    const double latency_us = (per_cu / resident) * (cps + 2) * t.lone_us;
     double us = kLaunchUs + (mfma_us > latency_us ? mfma_us : latency_us);
     if (ks_eff > 1) {
         // second launch; partial tiles written and read back

@@ -296,9 +296,22 @@ __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs 
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int co = (int)(idx / mquads), mq = 4 * (int)(idx - (int64_t)co * mquads);
     if (co >= p.K || mq >= g.Mtot) return;
+    // eight partial tiles in flight at a time; the sum runs in split order whatever the batching
+    const float* src = p.ws + (int64_t)co * g.Mpad + mq;
+    const int64_t step = (int64_t)g.Kpad * g.Mpad;
     f32x4 v = zero4();
-    for (int s = 0; s < g.ksplit; ++s) {
-        const f32x4 t = ldg4(p.ws + ((int64_t)s * g.Kpad + co) * g.Mpad + mq);
+    int s = 0;
+    for (; s + 8 <= g.ksplit; s += 8) {
+        f32x4 t[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = ldg4(src + (s + i) * step);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += t[i][r];
+    }
+    for (; s < g.ksplit; ++s) {
+        const f32x4 t = ldg4(src + s * step);
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] += t[r];
     }
