@@ -1,5 +1,7 @@
 // Variant table and shape-driven selection for the implicit-GEMM convolution
 // (kernel and its description in conv_igemm_kernel.h).
+#include <cstdlib>
+
 #include "conv_igemm_kernel.h"
 
 namespace anr {
@@ -76,11 +78,26 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
 
 }  // namespace
 
+// The tuned kernel has no split of the reduction across work-groups: with few output tiles
+// (batch 1) most CUs would idle, and the general kernel with split-K is faster.
+constexpr int kMinTunedWorkGroups = 112;
+
+// ANR_CONV_MIN_TUNED_WGS in the environment overrides the threshold (0: always the tuned kernel
+// when it can run the shape; a huge value: never).  Read at every call, so a test can switch it.
+int min_tuned_work_groups()
+{
+    const char* e = std::getenv("ANR_CONV_MIN_TUNED_WGS");
+    if (!e || !*e) return kMinTunedWorkGroups;
+    const long v = std::strtol(e, nullptr, 10);
+    return v < 0 ? 0 : (v > (1 << 30) ? (1 << 30) : (int)v);
+}
+
 bool conv2d_igemm_takes(const ConvArgs& a)
 {
     Geom g;
     size_t lds = 0;
-    return select_variant(a, &g, &lds) >= 0;
+    if (select_variant(a, &g, &lds) < 0) return false;
+    return (int64_t)g.tiles_m * g.tiles_n >= min_tuned_work_groups();
 }
 
 hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken)
@@ -89,7 +106,7 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
     Geom g;
     size_t lds = 0;
     const int best = select_variant(a, &g, &lds);
-    if (best < 0) return hipSuccess;
+    if (best < 0 || (int64_t)g.tiles_m * g.tiles_n < min_tuned_work_groups()) return hipSuccess;
     *taken = true;
     hipError_t err = hipSuccess;
     switch (best) {

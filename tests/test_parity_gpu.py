@@ -153,9 +153,18 @@ CONV_GENERIC = [
 ]
 
 
+@pytest.fixture(params=["tuned", "general"])
+def conv_route(request, monkeypatch):
+    """Runs a test once with the tuned patch-staging kernel wherever it can take the shape
+    and once with the general gather kernel for everything (the library reads the variable
+    at every call; by default the choice depends on the number of output tiles)."""
+    monkeypatch.setenv("ANR_CONV_MIN_TUNED_WGS", "0" if request.param == "tuned" else "1000000000")
+    return request.param
+
+
 @pytest.mark.parametrize("shape", CONV_FAST + CONV_GENERIC, ids=str)
 @pytest.mark.parametrize("ints", [False, True])
-def test_conv2d_small(anr, shape, ints):
+def test_conv2d_small(anr, conv_route, shape, ints):
     x, w = I.conv_inputs(shape, 200, ints=ints)
     buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
     anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad)
@@ -216,7 +225,7 @@ def test_conv2d_gather_strided_views(anr):
 
 
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
-def test_conv2d_configs(anr, name):
+def test_conv2d_configs(anr, conv_route, name):
     cfg = I.config_inputs(name)
     s = cfg["shape"]
     buf, y = guarded((s.N, s.K, s.OH, s.OW))
@@ -234,7 +243,7 @@ def test_conv2d_configs_integer_exact(anr, name):
     assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), exact=True, what=name + " ints")
 
 
-def test_conv2d_delta_kernel_is_shift(anr):
+def test_conv2d_delta_kernel_is_shift(anr, conv_route):
     C, H, W = 8, 12, 16
     x = I.small_ints(np.random.Generator(np.random.PCG64(5)), (2, C, H, W))
     for (r0, s0) in [(0, 0), (0, 2), (2, 1), (1, 1)]:
@@ -252,7 +261,7 @@ def test_conv2d_delta_kernel_is_shift(anr):
         assert np.array_equal(y.cpu().numpy(), exp)
 
 
-def test_conv2d_strided_views(anr):
+def test_conv2d_strided_views(anr, conv_route):
     # x is a window of a larger tensor and y is written into a larger tensor
     s = I.ConvShape(2, 8, 12, 16, 16, 3, 3, (1, 1), (1, 1))
     x, w = I.conv_inputs(s, 202)
@@ -292,7 +301,7 @@ CONVLAYER_SHAPES = [
 
 
 @pytest.mark.parametrize("shape", CONVLAYER_SHAPES, ids=str)
-def test_conv_bn_relu_small(anr, shape):
+def test_conv_bn_relu_small(anr, conv_route, shape):
     x, w = I.conv_inputs(shape, 300)
     w = (w * 4).astype(np.float32)     # spread the pre-activation so that both ReLU branches are hit
     gamma, beta, mean, var = I.bn_inputs(shape.K, 301)
