@@ -207,6 +207,25 @@ def shape_list(anr, I, torch):
     return rows
 
 
+def trace_summary(db_path):
+    """Per-kernel launch statistics from the rocpd database that `rocprofv3 --kernel-trace`
+    writes: calls, average / minimum / median duration in microseconds."""
+    import collections
+    import re
+    import sqlite3
+    import statistics
+    con = sqlite3.connect(db_path)
+    per = collections.defaultdict(list)
+    for name, start, end in con.execute("select name, start, end from kernels"):
+        per[name].append(end - start)
+    lines = ["%-90s %6s %10s %10s %10s" % ("kernel", "calls", "avg_us", "min_us", "med_us")]
+    for name, v in sorted(per.items(), key=lambda kv: -sum(kv[1])):
+        short = re.sub(r"\(anonymous namespace\)::", "", name)[:90]
+        lines.append("%-90s %6d %10.2f %10.2f %10.2f" % (short, len(v), sum(v) / len(v) / 1e3, min(v) / 1e3,
+                                                         statistics.median(v) / 1e3))
+    return "\n".join(lines)
+
+
 def oracle_reference(I, host, name):
     import oracle
     c = host["TBG" if name == "TBS" else name]
@@ -259,7 +278,12 @@ def main():
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--shape-list", action="store_true",
                     help="instead of the step, time every Appendix C shape at batch 1 and 16 and print one JSON line")
+    ap.add_argument("--trace-summary", default=None, metavar="DB",
+                    help="print per-kernel statistics of a rocprofv3 --kernel-trace database (no GPU needed) and exit")
     args = ap.parse_args()
+    if args.trace_summary:
+        print(trace_summary(args.trace_summary))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU figures are not produced",
               file=sys.stderr)

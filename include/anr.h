@@ -19,9 +19,15 @@
  *     with row extents/strides that are multiples of 4 elements select the
  *     vectorised kernels; anything else runs a slower kernel with the same
  *     results.
- *   - `ws`/`ws_bytes` is an optional device workspace.  anr_workspace_size()
- *     says how many bytes an operation wants (0 for every operation in this
- *     version); ws may be NULL when that is 0.
+ *   - `ws`/`ws_bytes` is a device workspace owned by the caller, 16-byte
+ *     aligned.  anr_workspace_size() says how many bytes an operation may
+ *     want for a descriptor; ws may be NULL when that is 0.  Only the
+ *     convolutions use one, and only for shapes with few output tiles and a
+ *     long reduction (batch 1, 7x7 maps), whose reduction is split over
+ *     work-groups that leave partial tiles there; its contents on entry do
+ *     not matter and are undefined on return.  A call that needs more than
+ *     it is given returns ANR_ERR_WORKSPACE.  Calls that share one workspace
+ *     must be ordered (same stream).
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is launched, so an invalid call has no effect on the device.
  *   - Thread-safe and re-entrant: the only state is a thread-local copy of the last
@@ -140,14 +146,17 @@ anr_status anr_dwconv(const anr_conv_desc *desc, const float *x, const float *w,
 anr_status anr_tbg(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Full TBS (Sec. 7.2, Appendix C "TBS"): anr_tbg followed by a softmax over j
- * (max-subtracted, in place on `out`, a second kernel on the same stream).
+/* Full TBS (Sec. 7.2, Appendix C "TBS"): the scores of anr_tbg followed by a
+ * softmax over j (max-subtracted): out[b,h,i,:] = softmax_j(sum_d q.k).  One
+ * fused kernel when S <= 128 and D is a multiple of 8 up to 128; otherwise the
+ * anr_tbg kernel and an in-place softmax kernel on the same stream.
  * Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
 anr_status anr_tbs(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Bytes of device workspace `op` (an anr_op) wants for `desc` (the matching
- * descriptor type).  Writes 0 when none is needed.  Validates the descriptor
+/* Bytes of device workspace `op` (an anr_op) may want for `desc` (the matching
+ * descriptor type): an upper bound that depends on the shape only, not on
+ * pointer alignment.  Writes 0 when none is needed.  Validates the descriptor
  * the same way the operation does. */
 anr_status anr_workspace_size(int op, const void *desc, size_t *bytes);
 
