@@ -11,6 +11,7 @@
 // consecutive k of "its" row with one ds_read_b128 and spends them on four MFMAs.
 #include "anr_device.h"
 #include "anr_kernels.h"
+#include "gemm_pipe_kernel.h"
 
 namespace anr {
 namespace {
@@ -137,6 +138,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs p)
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nk) load_tiles(kt + 1);
+        // keep the loads ahead of the MFMAs: the scheduler would sink them to their first use
+        // (the LDS stores after the loop) and their latency would not overlap the tile's MFMAs
+        __builtin_amdgcn_sched_barrier(0);
 
         const float* as = As[buf];
         const float* bs = Bs[buf];
@@ -393,6 +397,36 @@ hipError_t launch_variant(const GemmArgs& a, hipStream_t stream)
 }
 
 
+template <int BM, int BN, bool NT>
+hipError_t launch_pipe(const GemmArgs& a, hipStream_t stream)
+{
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const size_t lds_bytes = gpipe::Tiles<BM, BN, NT>::lds_bytes;
+    auto kern = gpipe::gemm_pipe_kernel<BM, BN, NT>;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    return launch_kernel(kern, dim3((unsigned)(tiles_m * tiles_n), 1, a.batch), dim3(256), lds_bytes, stream, a,
+                         tiles_m, tiles_n);
+}
+
+// Tile for the pipelined kernel: the largest that still puts two work-groups on every CU (they
+// fill each other's barrier and staging bubbles: 82 % MFMA utilisation against 55 % for a lone
+// work-group); large tiles pull fewer bytes per FLOP through the ~12 B/clk a CU can ingest,
+// 64 x 64 tiles are bound by exactly that.
+template <bool NT>
+hipError_t launch_pipe_any(const GemmArgs& a, hipStream_t stream)
+{
+    auto tiles = [&](int bm, int bn) {
+        return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.batch;
+    };
+    if (tiles(128, 128) >= 512) return launch_pipe<128, 128, NT>(a, stream);
+    if (tiles(128, 64) >= 512) return launch_pipe<128, 64, NT>(a, stream);
+    return launch_pipe<64, 64, NT>(a, stream);
+}
+
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
@@ -416,7 +450,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
     }
 
     hipError_t err;
-    if (a.b_is_nk) {
+    // 32-bit byte offsets inside one matrix, grid limits
+    const int64_t a_ext = (int64_t)(a.M - 1) * a.lda + a.K;
+    const int64_t b_ext = a.b_is_nk ? (int64_t)(a.N - 1) * a.ldb + a.K : (int64_t)(a.K - 1) * a.ldb + a.N;
+    const bool pipe = vec && a_ext < ((int64_t)1 << 29) && b_ext < ((int64_t)1 << 29) && a.batch <= 65535 &&
+                      (int64_t)((a.M + 63) / 64) * ((a.N + 63) / 64) < ((int64_t)1 << 31);
+    if (pipe && !a.b_is_nk) {
+        err = launch_pipe_any<false>(a, stream);
+    } else if (a.b_is_nk) {
         if (big) err = vec ? launch_variant<128, 128, 16, true, true>(a, stream)
                            : launch_variant<128, 128, 16, true, false>(a, stream);
         else     err = vec ? launch_variant<64, 64, 16, true, true>(a, stream)

@@ -103,6 +103,20 @@ def test_gemm_batched_and_strided(anr):
     assert bool((Cw[:, :2] == CANARY).all()) and bool((Cw[:, 54:] == CANARY).all())
 
 
+@pytest.mark.parametrize("M,N,K,batch", [(1024, 1024, 64, 8),      # 128 x 128 tiles of the pipelined kernel
+                                          (1000, 1000, 100, 4),     # 128 x 64 tiles, ragged rows and columns
+                                          (300, 200, 36, 3),        # 64 x 64 tiles, two chunks, ragged
+                                          (64, 64, 4, 1)])          # a single short chunk
+@pytest.mark.parametrize("ints", [False, True])
+def test_gemm_pipelined_tiles(anr, M, N, K, batch, ints):
+    A, B = I.gemm_inputs(I.GemmShape(M, N, K, batch), 110, ints=ints)
+    shape = (batch, M, N) if batch > 1 else (M, N)
+    buf, C = guarded(shape)
+    anr.gemm(dev(A), dev(B), C)
+    check_guard(buf)
+    assert_parity(C, oracle.gemm(A, B), exact=ints, what="gemm %dx%dx%d b%d" % (M, N, K, batch))
+
+
 def test_gemm_identity_returns_a(anr):
     A, _ = I.gemm_inputs(I.GemmShape(96, 96, 96), 9)
     C = torch.empty((96, 96), device="cuda")
