@@ -23,7 +23,7 @@ hipError_t launch_rows(const ConvArgs& a, hipStream_t stream)
 
 hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
-    const bool ok = a.R == 3 && a.S == 3 && a.stride_h == 1 && a.stride_w == 1 && a.pad_h == 1 &&
+    const bool ok = a.R == 3 && a.S == 3 && a.dil_h == 1 && a.dil_w == 1 && a.stride_h == 1 && a.stride_w == 1 && a.pad_h == 1 &&
                     a.pad_w == 1 && (a.W % 4 == 0) && a.W <= 256 && is_aligned16(a.x) &&
                     is_aligned16(a.y) && (a.xs[0] % 4 == 0) && (a.xs[1] % 4 == 0) &&
                     (a.xs[2] % 4 == 0) && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) &&

@@ -366,6 +366,17 @@ DW_SHAPES = [
     I.ConvShape(1, 4, 17, 20, 4, 3, 3, (2, 2), (1, 1)),
     I.ConvShape(1, 3, 9, 10, 3, 5, 5, (1, 1), (2, 2)),
     I.ConvShape(1, 2, 6, 260, 2, 3, 3, (1, 1), (1, 1)),
+    # general kernel: small planes, rows wider than a wave, tall images, asymmetric stride and
+    # padding, kernels that hang over the image edge
+    I.ConvShape(3, 67, 7, 7, 67, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 9, 14, 14, 9, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 3, 112, 112, 3, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 2, 150, 70, 2, 3, 3, (1, 1), (1, 1)),
+    I.ConvShape(2, 3, 40, 130, 3, 5, 3, (2, 1), (2, 0)),
+    I.ConvShape(1, 5, 9, 11, 5, 7, 7, (1, 1), (3, 3)),
+    I.ConvShape(1, 4, 5, 5, 4, 5, 5, (1, 1), (4, 4)),
+    I.ConvShape(1, 1, 64, 64, 1, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(1, 3, 20, 65, 3, 2, 4, (3, 2), (1, 2)),
 ]
 
 
