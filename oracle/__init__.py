@@ -43,6 +43,8 @@ def _load():
     conv_args = [_int] * 11
     lib.orc_conv2d.argtypes = conv_args + [_f32p, _f32p, _f64p]
     lib.orc_conv2d.restype = None
+    lib.orc_conv2d_general.argtypes = [_int] * 14 + [_f32p, _f32p, _f64p]
+    lib.orc_conv2d_general.restype = _int
     lib.orc_conv_bn_relu.argtypes = conv_args + [_f32p, _f32p, _f32p, _f32p, _f32p, _f32p,
                                                  ctypes.c_float, _f64p]
     lib.orc_conv_bn_relu.restype = None
@@ -117,6 +119,27 @@ def conv2d(x, w, stride=(1, 1), pad=(0, 0)):
     y = np.empty((N, K, OH, OW), dtype=np.float64)
     _load().orc_conv2d(N, C, H, W, K, R, S, stride[0], stride[1], pad[0], pad[1],
                        _p32(x), _p32(w), _p64(y))
+    return y
+
+
+def conv2d_general(x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1):
+    """Grouped and / or dilated convolution (the GRP and DIL operators): x [N,C,H,W],
+    w [K, C/groups, R, S] -> y [N,K,OH,OW]."""
+    x = _f32(x)
+    w = _f32(w)
+    N, C, H, W = x.shape
+    K, Cg, R, S = w.shape
+    if groups < 1 or C % groups or K % groups or Cg != C // groups:
+        raise ValueError("channel counts do not match the group count")
+    OH = out_extent(H, pad[0], dil[0] * (R - 1) + 1, stride[0])
+    OW = out_extent(W, pad[1], dil[1] * (S - 1) + 1, stride[1])
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    y = np.empty((N, K, OH, OW), dtype=np.float64)
+    rc = _load().orc_conv2d_general(N, C, H, W, K, R, S, stride[0], stride[1], pad[0], pad[1],
+                                    dil[0], dil[1], groups, _p32(x), _p32(w), _p64(y))
+    if rc != 0:
+        raise ValueError("orc_conv2d_general rejected the shape")
     return y
 
 

@@ -144,6 +144,57 @@ void orc_conv_bn_relu(int N, int C, int H, int W, int K, int R, int S,
 }
 
 /*
+ * GRP and DIL, Sec. 7.1 / Appendix C (fields as C2D plus "groups", resp.
+ * "dilation"): the convolution above with the two generalisations the paper's
+ * operator list names.
+ *   dilation d: tap (r, s) reads input row oh*stride - pad + r*d_h and column
+ *     ow*stride - pad + s*d_w; output extent
+ *     floor((H + 2*pad - d*(R-1) - 1)/stride) + 1.
+ *   groups g: input and output channels are cut into g equal runs; output
+ *     channel k of run k / (K/g) only sees the C/g input channels of the same
+ *     run.  w is [K, C/g, R, S].
+ * g = 1, d = 1 is orc_conv2d.  Returns 0, or -1 when C or K is not a multiple
+ * of the group count.
+ */
+int orc_conv2d_general(int N, int C, int H, int W, int K, int R, int S,
+                       int stride_h, int stride_w, int pad_h, int pad_w,
+                       int dil_h, int dil_w, int groups,
+                       const float *x, const float *w, double *y)
+{
+    if (groups < 1 || C % groups != 0 || K % groups != 0) return -1;
+    const int Cg = C / groups, Kg = K / groups;
+    const int OH = (H + 2 * pad_h - dil_h * (R - 1) - 1) / stride_h + 1;
+    const int OW = (W + 2 * pad_w - dil_w * (S - 1) - 1) / stride_w + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int k = 0; k < K; ++k) {
+            const int g = k / Kg;
+            for (int oh = 0; oh < OH; ++oh) {
+                for (int ow = 0; ow < OW; ++ow) {
+                    double acc = 0.0;
+                    for (int cg = 0; cg < Cg; ++cg) {
+                        const int c = g * Cg + cg;
+                        for (int r = 0; r < R; ++r) {
+                            const int ih = oh * stride_h - pad_h + r * dil_h;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int s = 0; s < S; ++s) {
+                                const int iw = ow * stride_w - pad_w + s * dil_w;
+                                if (iw < 0 || iw >= W) continue;
+                                const double xv = x[(((size_t)n * C + c) * H + ih) * W + iw];
+                                const double wv = w[(((size_t)k * Cg + cg) * R + r) * S + s];
+                                acc += xv * wv;
+                            }
+                        }
+                    }
+                    y[(((size_t)n * K + k) * OH + oh) * OW + ow] = acc;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * DEP, Sec. 7.1 / Appendix C (fields: height, width, channels, kernel size,
  * stride, padding): depthwise convolution with channel multiplier 1.  Channel
  * c of the output only sees channel c of the input.  w is [C,1,R,S].

@@ -200,6 +200,140 @@ DW_CASES = [
 ]
 
 
+# ---------------------------------------------------------------- grouped / dilated conv2d
+def expand_kernel(w, dil):
+    """The dilated kernel written out: zeros between the taps."""
+    K, C, R, S = w.shape
+    e = np.zeros((K, C, dil[0] * (R - 1) + 1, dil[1] * (S - 1) + 1), w.dtype)
+    e[:, :, ::dil[0], ::dil[1]] = w
+    return e
+
+
+GENERAL_CASES = [   # N, C, H, W, K, R, S, stride, pad, dil, groups
+    (2, 4, 9, 8, 6, 3, 3, (1, 1), (2, 2), (2, 2), 1),
+    (1, 3, 15, 14, 4, 3, 2, (2, 1), (1, 3), (3, 2), 1),
+    (2, 6, 7, 7, 4, 3, 3, (1, 1), (1, 1), (1, 1), 2),
+    (1, 8, 6, 9, 12, 1, 1, (1, 1), (0, 0), (1, 1), 4),
+    (1, 4, 11, 10, 8, 3, 3, (2, 2), (2, 2), (2, 2), 4),
+]
+
+
+def general_inputs(case, seed):
+    N, C, H, W, K, R, S, stride, pad, dil, groups = case
+    g = rng(seed)
+    return I.uniform(g, (N, C, H, W)), I.normal(g, (K, C // groups, R, S), 0.5)
+
+
+@pytest.mark.parametrize("case", GENERAL_CASES, ids=str)
+def test_conv2d_general_vs_windows(case):
+    # second derivation: pad explicitly, take the strided, dilated window of each output pixel
+    # from the channels of its group, contract with einsum.  Catches dilation applied to the
+    # pixel instead of the tap, a wrong group of input channels, a wrong output extent.
+    N, C, H, W, K, R, S, stride, pad, dil, groups = case
+    x, w = general_inputs(case, 31)
+    got = oracle.conv2d_general(x, w, stride, pad, dil, groups)
+    xp = np.pad(x.astype(np.float64), ((0, 0), (0, 0), (pad[0], pad[0]), (pad[1], pad[1])))
+    OH = (H + 2 * pad[0] - dil[0] * (R - 1) - 1) // stride[0] + 1
+    OW = (W + 2 * pad[1] - dil[1] * (S - 1) - 1) // stride[1] + 1
+    assert got.shape == (N, K, OH, OW)
+    Cg, Kg = C // groups, K // groups
+    ref = np.zeros((N, K, OH, OW))
+    for g in range(groups):
+        for oh in range(OH):
+            for ow in range(OW):
+                win = xp[:, g * Cg:(g + 1) * Cg,
+                         oh * stride[0]:oh * stride[0] + dil[0] * (R - 1) + 1:dil[0],
+                         ow * stride[1]:ow * stride[1] + dil[1] * (S - 1) + 1:dil[1]]
+                ref[:, g * Kg:(g + 1) * Kg, oh, ow] = np.einsum("ncrs,kcrs->nk", win,
+                                                                w[g * Kg:(g + 1) * Kg].astype(np.float64))
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("shape", CONV_CASES, ids=str)
+def test_conv2d_general_reduces_to_conv2d(shape):
+    # one group, no dilation: the same loops in the same order as the C2D oracle
+    x, w = I.conv_inputs(shape, 32)
+    assert np.array_equal(oracle.conv2d_general(x, w, shape.stride, shape.pad, (1, 1), 1),
+                          oracle.conv2d(x, w, shape.stride, shape.pad))
+
+
+@pytest.mark.parametrize("case", GENERAL_CASES[:2], ids=str)
+def test_dilated_conv_is_conv_with_zero_filled_kernel(case):
+    # the dilated kernel written out with zeros between its taps, through the C2D oracle: the
+    # zero products add nothing, so the sums agree exactly
+    N, C, H, W, K, R, S, stride, pad, dil, groups = case
+    x, w = general_inputs(case, 33)
+    assert np.array_equal(oracle.conv2d_general(x, w, stride, pad, dil, 1),
+                          oracle.conv2d(x, expand_kernel(w, dil), stride, pad))
+
+
+def test_dilated_delta_kernel_shifts_by_dilated_tap():
+    # 1 at tap (r0,s0): the image shifted by (r0*d - pad, s0*d - pad), exactly
+    C, H, W, p, d = 2, 8, 9, 2, 2
+    x = I.small_ints(rng(34), (1, C, H, W))
+    for r0, s0 in [(0, 0), (2, 1), (1, 2)]:
+        w = np.zeros((C, C, 3, 3), np.float32)
+        for c in range(C):
+            w[c, c, r0, s0] = 1.0
+        y = oracle.conv2d_general(x, w, (1, 1), (p, p), (d, d), 1)
+        assert y.shape == (1, C, H, W)
+        exp = np.zeros_like(y)
+        for oh in range(H):
+            for ow in range(W):
+                ih, iw = oh + r0 * d - p, ow + s0 * d - p
+                if 0 <= ih < H and 0 <= iw < W:
+                    exp[:, :, oh, ow] = x[:, :, ih, iw]
+        assert np.array_equal(y, exp)
+
+
+def test_dilated_all_ones_counts_valid_taps_and_extent():
+    # dilation 2, pad 2, 3x3: taps at -2, 0, +2; corner 4, edge 6, interior 9 per channel
+    C = 3
+    x = np.ones((1, C, 7, 7), np.float32)
+    w = np.ones((1, C, 3, 3), np.float32)
+    y = oracle.conv2d_general(x, w, (1, 1), (2, 2), (2, 2), 1)
+    assert y.shape == (1, 1, 7, 7)
+    assert y[0, 0, 0, 0] == 4 * C and y[0, 0, 0, 3] == 6 * C and y[0, 0, 3, 3] == 9 * C
+    assert y[0, 0, 1, 1] == 4 * C      # row 1: taps at -1 (out), 1, 3
+    # the stem shape of the appendix with dilation 2: (224 + 6 - 13) // 2 + 1
+    xs = np.zeros((1, 1, 224, 224), np.float32)
+    assert oracle.conv2d_general(xs, np.zeros((1, 1, 7, 7), np.float32), (2, 2), (3, 3), (2, 2), 1).shape[2:] == (109, 109)
+
+
+@pytest.mark.parametrize("case", GENERAL_CASES[2:], ids=str)
+def test_grouped_conv_is_block_diagonal_conv(case):
+    # the grouped weights placed on the diagonal blocks of a dense [K,C,R,S] kernel, through the
+    # dilated single-group path: catches k % groups instead of k / (K/groups), a shifted run
+    N, C, H, W, K, R, S, stride, pad, dil, groups = case
+    x, w = general_inputs(case, 35)
+    Cg, Kg = C // groups, K // groups
+    dense = np.zeros((K, C, R, S), np.float32)
+    for g in range(groups):
+        dense[g * Kg:(g + 1) * Kg, g * Cg:(g + 1) * Cg] = w[g * Kg:(g + 1) * Kg]
+    assert np.array_equal(oracle.conv2d_general(x, w, stride, pad, dil, groups),
+                          oracle.conv2d_general(x, dense, stride, pad, dil, 1))
+
+
+def test_grouped_conv_with_one_channel_per_group_is_depthwise():
+    s = I.ConvShape(2, 5, 8, 7, 5, 3, 3, (1, 1), (1, 1))
+    x, w = I.dwconv_inputs(s, 36)
+    assert np.array_equal(oracle.conv2d_general(x, w, s.stride, s.pad, (1, 1), s.C),
+                          oracle.dwconv(x, w, s.stride, s.pad))
+
+
+def test_grouped_conv_groups_do_not_mix():
+    case = GENERAL_CASES[2]
+    x, w = general_inputs(case, 37)
+    y = oracle.conv2d_general(x, w, case[7], case[8], case[9], 2)
+    x2 = x.copy()
+    x2[:, 3:] += 1.0                     # second group's input channels only
+    y2 = oracle.conv2d_general(x2, w, case[7], case[8], case[9], 2)
+    assert np.array_equal(y[:, :2], y2[:, :2]) and not np.array_equal(y[:, 2:], y2[:, 2:])
+    with pytest.raises(ValueError):
+        oracle.conv2d_general(x, w[:, :2], case[7], case[8], case[9], 4)
+
+
+# ---------------------------------------------------------------- dwconv
 @pytest.mark.parametrize("shape", DW_CASES, ids=str)
 def test_dwconv_equals_block_diagonal_conv2d(shape):
     # depthwise == dense conv whose weights are zero off the channel diagonal
