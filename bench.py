@@ -161,10 +161,12 @@ def shape_list(anr, I, torch):
     rnd = lambda *shape: torch.rand(shape, generator=gen, device="cuda", dtype=torch.float32) * 2 - 1
     emp = lambda *shape: torch.empty(shape, device="cuda", dtype=torch.float32)
     rows = []
-    for op in ("GMM", "C2D", "DEP", "ConvLayer", "TBS"):
+    for op in ("GMM", "C2D", "DEP", "ConvLayer", "TBS", "GRP", "DIL"):
         for fields in I.APPENDIX_C[op]:
             for batch in I.BATCHES:
                 s = I.appendix_shape(op, fields, batch)
+                if s is None:          # a record that cannot be built (3 channels in 4 groups)
+                    continue
                 if op == "GMM":
                     flops = 2.0 * s.batch * s.M * s.N * s.K
                     nbytes = 4.0 * s.batch * (s.M * s.K + s.K * s.N + s.M * s.N)
@@ -177,7 +179,7 @@ def shape_list(anr, I, torch):
                     run = lambda t: anr.tbs(t[0], t[1], t[2])
                 else:
                     dw = op == "DEP"
-                    cin = 1 if dw else s.C
+                    cin = 1 if dw else s.C // s.groups
                     flops = 2.0 * s.N * s.K * s.OH * s.OW * cin * s.R * s.S
                     nbytes = 4.0 * (s.N * s.C * s.H * s.W + s.K * cin * s.R * s.S + s.N * s.K * s.OH * s.OW)
                     if op == "ConvLayer":
@@ -189,8 +191,8 @@ def shape_list(anr, I, torch):
                         mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.C, 1, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
                         run = lambda t: anr.dwconv(t[0], t[1], t[2], s.stride, s.pad)
                     else:
-                        mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.K, s.C, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
-                        run = lambda t: anr.conv2d(t[0], t[1], t[2], s.stride, s.pad)
+                        mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.K, cin, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
+                        run = lambda t: anr.conv2d(t[0], t[1], t[2], s.stride, s.pad, dil=s.dil, groups=s.groups)
                 # enough buffer sets that a launch does not find its data in the 256 MB Infinity Cache
                 nsets = int(min(12, max(2, -(-320e6 // nbytes))))
                 sets = [mk() for _ in range(nsets)]

@@ -74,20 +74,27 @@ typedef struct {
 } anr_gemm_desc;
 
 /*
- * Convolution geometry shared by C2D, ConvLayer and DEP.
- *   x [N,C,H,W], y [N,K,OH,OW] with OH = floor((H + 2*pad_h - R)/stride_h) + 1
- *   (OW alike).  Cross-correlation (no kernel flip); zero padding, the same
- *   amount on both sides.  K is the number of output channels; for the
- *   depthwise call K must equal C (channel multiplier 1).
- *   Weights are always packed: OIHW [K,C,R,S] for conv2d / conv_bn_relu,
- *   [C,1,R,S] for dwconv.
+ * Convolution geometry shared by C2D, ConvLayer, DEP and the GRP / DIL
+ * variants of C2D (Sec. 7.1, Appendix C).
+ *   x [N,C,H,W], y [N,K,OH,OW] with
+ *   OH = floor((H + 2*pad_h - dil_h*(R-1) - 1)/stride_h) + 1 (OW alike).
+ *   Cross-correlation (no kernel flip); tap (r,s) reads input row
+ *   oh*stride_h - pad_h + r*dil_h; zero padding, the same amount on both
+ *   sides.  K is the number of output channels; for the depthwise call K
+ *   must equal C (channel multiplier 1).
+ *   groups (0 means 1): input and output channels are cut into `groups`
+ *   equal runs and output channel k only sees the C/groups input channels of
+ *   run k / (K/groups); C and K must be multiples of it.  The depthwise call
+ *   ignores the field.
+ *   Weights are always packed: OIHW [K, C/groups, R, S] for conv2d /
+ *   conv_bn_relu, [C,1,R,S] for dwconv.
  *   x_stride / y_stride are element strides for (n, c, h, w).  All four zero
  *   means packed NCHW.  Otherwise every stride must be >= 1 and the view must
  *   not alias itself (w-stride 1 is required by this version: anything else
  *   returns ANR_ERR_UNSUPPORTED).
- *   dil_h, dil_w must be 1 and layout must be ANR_LAYOUT_NCHW (else
- *   ANR_ERR_UNSUPPORTED).  pad >= 0, stride >= 1, pad < kernel extent is NOT
- *   required.  OH <= 0 or OW <= 0 is ANR_ERR_INVALID_ARG.
+ *   layout must be ANR_LAYOUT_NCHW (else ANR_ERR_UNSUPPORTED).  pad >= 0,
+ *   stride >= 1, dil >= 1; pad < kernel extent is NOT required.  OH <= 0 or
+ *   OW <= 0 is ANR_ERR_INVALID_ARG.
  */
 typedef struct {
     int32_t N, C, H, W;
@@ -98,6 +105,8 @@ typedef struct {
     int32_t layout;
     int64_t x_stride[4];
     int64_t y_stride[4];
+    int32_t groups;      /* 0 or 1: ordinary convolution */
+    int32_t reserved;    /* must be 0 */
 } anr_conv_desc;
 
 /*

@@ -143,6 +143,17 @@ def conv2d_general(x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1):
     return y
 
 
+def conv_bn_relu_general(x, w, gamma, beta, mean, var, eps, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1):
+    """ConvLayer (Sec. 7.2) over the grouped / dilated convolution: conv2d_general, then per output
+    channel gamma * (v - mean) / sqrt(var + eps) + beta, then max(., 0), in float64 with every
+    parameter widened from its float32 value."""
+    v = conv2d_general(x, w, stride, pad, dil, groups)
+    K = v.shape[1]
+    g, b, m, s2 = (_f32(t, (K,)).astype(np.float64)[None, :, None, None] for t in (gamma, beta, mean, var))
+    y = g * (v - m) / np.sqrt(s2 + np.float64(np.float32(eps))) + b
+    return np.maximum(y, 0.0)
+
+
 def conv_bn_relu(x, w, gamma, beta, mean, var, eps, stride=(1, 1), pad=(0, 0)):
     x = _f32(x)
     w = _f32(w)

@@ -46,7 +46,8 @@ class ConvDesc(ctypes.Structure):
                 ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32),
                 ("dil_h", ctypes.c_int32), ("dil_w", ctypes.c_int32),
                 ("layout", ctypes.c_int32),
-                ("x_stride", ctypes.c_int64 * 4), ("y_stride", ctypes.c_int64 * 4)]
+                ("x_stride", ctypes.c_int64 * 4), ("y_stride", ctypes.c_int64 * 4),
+                ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class TbgDesc(ctypes.Structure):
@@ -116,9 +117,10 @@ def _stream():
 
 
 def conv_desc(x_shape, K, R, S, stride=(1, 1), pad=(0, 0), x_stride=None, y_stride=None, dil=(1, 1),
-              layout=ANR_LAYOUT_NCHW) -> ConvDesc:
+              layout=ANR_LAYOUT_NCHW, groups=1) -> ConvDesc:
     N, C, H, W = x_shape
     d = ConvDesc(N, C, H, W, K, R, S, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], layout)
+    d.groups = groups
     if x_stride is not None:
         d.x_stride = (ctypes.c_int64 * 4)(*x_stride)
     if y_stride is not None:
@@ -180,26 +182,26 @@ def _conv_strides(t):
     return None if t.is_contiguous() else tuple(t.stride())
 
 
-def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None):
-    """y = conv2d(x, w); x [N,C,H,W], w [K,C,R,S] packed, y [N,K,OH,OW] (may be strided views).
+def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1):
+    """y = conv2d(x, w); x [N,C,H,W], w [K,C/groups,R,S] packed, y [N,K,OH,OW] (may be strided views).
     ws: optional workspace tensor of at least workspace_size(ANR_OP_CONV2D, desc) bytes."""
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
-    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y))
+    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups)
     wp, wb = _workspace(ANR_OP_CONV2D, d, ws)
     _check(_lib.anr_conv2d(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), wp, wb, _stream()), "anr_conv2d")
     return y
 
 
-def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None):
+def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1):
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
     for v in (gamma, beta, mean, var):
         if tuple(v.shape) != (K,) or not v.is_contiguous():
             raise ValueError("batch-norm vectors must be packed [K]")
-    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y))
+    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups)
     wp, wb = _workspace(ANR_OP_CONV_BN_RELU, d, ws)
     _check(_lib.anr_conv_bn_relu(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(gamma), _ptr(beta), _ptr(mean),
                                  _ptr(var), ctypes.c_float(eps), _ptr(y), wp, wb, _stream()),
@@ -207,11 +209,11 @@ def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0)
     return y
 
 
-def dwconv(x, w, y, stride=(1, 1), pad=(0, 0)):
+def dwconv(x, w, y, stride=(1, 1), pad=(0, 0), dil=(1, 1)):
     C, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
-    d = conv_desc(tuple(x.shape), C, R, S, stride, pad, _conv_strides(x), _conv_strides(y))
+    d = conv_desc(tuple(x.shape), C, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil)
     _check(_lib.anr_dwconv(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), None, 0, _stream()), "anr_dwconv")
     return y
 

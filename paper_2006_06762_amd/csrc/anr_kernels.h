@@ -54,6 +54,7 @@ struct ConvArgs {
     int N, C, H, W, K, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dil_h, dil_w;
+    int groups;      // >= 1; weights are [K, C/groups, R, S] (ignored by the depthwise launchers)
     int OH, OW;
     int64_t xs[4];   // element strides n,c,h,w (w stride is 1)
     int64_t ys[4];

@@ -10,7 +10,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.1.0
 
 // HIP status of the most recent failed launch made by this thread (diagnostics only).
 thread_local int g_last_hip_error = 0;
@@ -38,10 +38,11 @@ anr_status check_conv(const anr_conv_desc* d, bool depthwise, ConvGeom* g)
     if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return ANR_ERR_INVALID_ARG;
     if (d->dil_h < 1 || d->dil_w < 1) return ANR_ERR_INVALID_ARG;
     if (depthwise && d->K != d->C) return ANR_ERR_INVALID_ARG;
-    if (d->dil_h != 1 || d->dil_w != 1) return ANR_ERR_UNSUPPORTED;
+    if (d->groups < 0 || d->reserved != 0) return ANR_ERR_INVALID_ARG;
+    if (!depthwise && d->groups > 1 && (d->C % d->groups != 0 || d->K % d->groups != 0)) return ANR_ERR_INVALID_ARG;
     if (d->layout != ANR_LAYOUT_NCHW) return ANR_ERR_UNSUPPORTED;
-    const int64_t eh = (int64_t)d->H + 2 * (int64_t)d->pad_h - d->R;
-    const int64_t ew = (int64_t)d->W + 2 * (int64_t)d->pad_w - d->S;
+    const int64_t eh = (int64_t)d->H + 2 * (int64_t)d->pad_h - (int64_t)d->dil_h * (d->R - 1) - 1;
+    const int64_t ew = (int64_t)d->W + 2 * (int64_t)d->pad_w - (int64_t)d->dil_w * (d->S - 1) - 1;
     if (eh < 0 || ew < 0) return ANR_ERR_INVALID_ARG;
     g->OH = (int)(eh / d->stride_h) + 1;
     g->OW = (int)(ew / d->stride_w) + 1;
@@ -86,6 +87,7 @@ anr::ConvArgs make_conv_args(const anr_conv_desc* d, const ConvGeom& g, const fl
     a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.dil_h = d->dil_h; a.dil_w = d->dil_w;
+    a.groups = d->groups > 1 ? d->groups : 1;
     a.OH = g.OH; a.OW = g.OW;
     for (int i = 0; i < 4; ++i) { a.xs[i] = g.xs[i]; a.ys[i] = g.ys[i]; }
     a.gamma = a.beta = a.mean = a.var = nullptr;

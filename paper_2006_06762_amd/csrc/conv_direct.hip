@@ -21,18 +21,20 @@ __global__ __launch_bounds__(256) void conv2d_direct_kernel(const ConvArgs p, in
     const int k = (int)(t % p.K);
     const int n = (int)(t / p.K);
 
-    const float* __restrict__ xn = p.x + n * p.xs[0];
-    const float* __restrict__ wk = p.w + (int64_t)k * p.C * p.R * p.S;
+    // output channel k belongs to group k / (K/groups) and sees that group's C/groups channels
+    const int cg = p.C / p.groups, grp = k / (p.K / p.groups);
+    const float* __restrict__ xn = p.x + n * p.xs[0] + (int64_t)grp * cg * p.xs[1];
+    const float* __restrict__ wk = p.w + (int64_t)k * cg * p.R * p.S;
     const int ih0 = oh * p.stride_h - p.pad_h, iw0 = ow * p.stride_w - p.pad_w;
     float acc = 0.f;
-    for (int c = 0; c < p.C; ++c) {
+    for (int c = 0; c < cg; ++c) {
         const float* __restrict__ xc = xn + c * p.xs[1];
         const float* __restrict__ wc = wk + (int64_t)c * p.R * p.S;
         for (int r = 0; r < p.R; ++r) {
-            const int ih = ih0 + r;
+            const int ih = ih0 + r * p.dil_h;
             if (ih < 0 || ih >= p.H) continue;
             for (int s = 0; s < p.S; ++s) {
-                const int iw = iw0 + s;
+                const int iw = iw0 + s * p.dil_w;
                 if (iw < 0 || iw >= p.W) continue;
                 acc = fmaf(xc[ih * p.xs[2] + iw], wc[r * p.S + s], acc);
             }
@@ -62,10 +64,10 @@ __global__ __launch_bounds__(256) void dwconv_direct_kernel(const ConvArgs p, in
     const int ih0 = oh * p.stride_h - p.pad_h, iw0 = ow * p.stride_w - p.pad_w;
     float acc = 0.f;
     for (int r = 0; r < p.R; ++r) {
-        const int ih = ih0 + r;
+        const int ih = ih0 + r * p.dil_h;
         if (ih < 0 || ih >= p.H) continue;
         for (int s = 0; s < p.S; ++s) {
-            const int iw = iw0 + s;
+            const int iw = iw0 + s * p.dil_w;
             if (iw < 0 || iw >= p.W) continue;
             acc = fmaf(xc[ih * p.xs[2] + iw], wc[r * p.S + s], acc);
         }

@@ -22,7 +22,7 @@ bool make_plan(const ConvArgs& a, Plan* g)
 {
     const int64_t x_extent = (int64_t)(a.N - 1) * a.xs[0] + (int64_t)(a.C - 1) * a.xs[1] +
                              (int64_t)(a.H - 1) * a.xs[2] + a.W;
-    const int64_t w_extent = (int64_t)a.K * a.C * a.R * a.S;
+    const int64_t w_extent = (int64_t)a.K * (a.C / a.groups) * a.R * a.S;
     const int64_t Mtot = (int64_t)a.N * a.OH * a.OW;
     // byte offsets must stay below the out-of-range marker of the buffer loads (2^31)
     if (x_extent >= ((int64_t)1 << 29) || w_extent >= ((int64_t)1 << 29) || Mtot >= ((int64_t)1 << 30))
@@ -35,7 +35,10 @@ bool make_plan(const ConvArgs& a, Plan* g)
     g->Mtot = (int)Mtot;
     g->ohow = a.OH * a.OW;
     g->RS = a.R * a.S;
-    g->Ktot = a.C * g->RS;
+    g->Cg = a.C / a.groups;
+    g->Kg = a.K / a.groups;
+    g->Ktot = g->Cg * g->RS;
+    g->d_kg = make_fastdiv(g->Kg);
     g->nchunks = (g->Ktot + KC - 1) / KC;
     g->w_vec = (g->Ktot % 4 == 0) && is_aligned16(a.w);
     g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) &&
@@ -57,7 +60,9 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     g->bm = bm;
     g->bn = bn;
     g->tiles_m = (g->Mtot + bm - 1) / bm;
-    g->tiles_n = (a.K + bn - 1) / bn;
+    g->tiles_ng = (g->Kg + bn - 1) / bn;
+    g->tiles_n = a.groups * g->tiles_ng;
+    g->d_tiles_ng = make_fastdiv(g->tiles_ng);
     if (ks > g->nchunks) ks = g->nchunks;
     g->chunks_per_split = (g->nchunks + ks - 1) / ks;
     g->ksplit = (g->nchunks + g->chunks_per_split - 1) / g->chunks_per_split;
@@ -74,7 +79,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
 // measurements on the shape lists of Appendix C.
 double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
 {
-    const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * ((a.K + t.bn - 1) / t.bn);
+    const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * a.groups * ((g.Kg + t.bn - 1) / t.bn);
     const int cps = (g.nchunks + ks - 1) / ks;
     const int ks_eff = (g.nchunks + cps - 1) / cps;
     const int64_t wgs = tiles * ks_eff;
@@ -97,7 +102,7 @@ bool choose_tile(const ConvArgs& a, Plan* g)
     bool have = false;
     int bm = 0, bn = 0, bks = 1;
     for (const Tile& t : kTiles) {
-        const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * ((a.K + t.bn - 1) / t.bn);
+        const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * a.groups * ((g->Kg + t.bn - 1) / t.bn);
         if (tiles >= ((int64_t)1 << 24)) continue;
         const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;      // enough tiles: no split
         int last_cps = 0;

@@ -41,13 +41,16 @@ constexpr int kNoRow = 0x7fff;                  // row displacement of a reducti
 constexpr int kMaxExtent = 16000;               // image height/width and kernel extents the tap table packs
 
 struct Plan {
-    int Mtot, ohow, Ktot, RS;
+    int Mtot, ohow, RS;
+    int Ktot;                    // reduction length: (C / groups) * R * S
+    int Cg, Kg;                  // input / output channels per group
+    int tiles_ng;                // column tiles per group (a tile never straddles two groups)
     int tiles_m, tiles_n, ksplit, nchunks, chunks_per_split;
     int Mpad, Kpad;              // tile-padded extents of the workspace
     int w_vec;                   // weight rows allow 16-byte loads
     int vec_store;               // 4 consecutive pixels of a lane are 16 contiguous, aligned bytes of y
     uint32_t x_bytes, w_bytes;
-    FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles;
+    FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles, d_tiles_ng, d_kg;
     int bm, bn;                  // chosen tile (host side)
 };
 
@@ -106,7 +109,9 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
     const int split = g.d_tiles.div((int)blockIdx.x);
     const int trem = (int)blockIdx.x - split * tiles;
     const int tile_n = g.d_tiles_m.div(trem), tile_m = trem - tile_n * g.tiles_m;
-    const int m0 = tile_m * BM, co0 = tile_n * BN;
+    const int grp = g.d_tiles_ng.div(tile_n);                        // channel group of this tile
+    const int m0 = tile_m * BM, cl0 = (tile_n - grp * g.tiles_ng) * BN;  // first column inside the group
+    const int cog = grp * g.Kg;                                      // first output channel of the group
     const int c_begin = split * g.chunks_per_split;
     const int c_end = c_begin + g.chunks_per_split < g.nchunks ? c_begin + g.chunks_per_split : g.nchunks;
 
@@ -121,7 +126,8 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
         const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
         ihb = oh * p.stride_h - p.pad_h;
         iwb = ow * p.stride_w - p.pad_w;
-        xbase = (int)(n * p.xs[0] + ihb * p.xs[2] + iwb);         // may be negative; valid taps make it >= 0
+        // may be negative; valid taps make it >= 0.  The group's first input channel is folded in.
+        xbase = (int)(n * p.xs[0] + (int64_t)grp * g.Cg * p.xs[1] + ihb * p.xs[2] + iwb);
     }
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
@@ -172,8 +178,8 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 #pragma unroll
             for (int j = 0; j < BU4; ++j) {
                 const int col = (tid >> 3) + 32 * j, k = k0 + 4 * (tid & 7);
-                int co = co0 + col;
-                co = co < p.K ? co : p.K - 1;                     // columns past K repeat the last, never stored
+                int co = cl0 + col;
+                co = cog + (co < g.Kg ? co : g.Kg - 1);           // columns past the group repeat its last, never stored
                 const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
                 const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0));
 #pragma unroll
@@ -183,8 +189,8 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 #pragma unroll
             for (int j = 0; j < BU1; ++j) {
                 const int col = (tid >> 5) + 8 * j, k = k0 + (tid & 31);
-                int co = co0 + col;
-                co = co < p.K ? co : p.K - 1;
+                int co = cl0 + col;
+                co = cog + (co < g.Kg ? co : g.Kg - 1);
                 const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
                 rb[set][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, (int)off, 0, 0));
             }
@@ -272,7 +278,7 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const int col = co0 + (wn * NB + nb) * 32 + r32;
+            const int tcol = (wn * NB + nb) * 32 + r32;             // column inside the tile
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int mq = m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h;
@@ -280,9 +286,9 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
                                  acc[mb][nb][4 * q + 3]};
                 if (g.ksplit > 1) {
                     // the workspace is padded to whole tiles: no bounds to test
-                    stg4(p.ws + ((int64_t)split * g.Kpad + col) * g.Mpad + mq, v);
-                } else if (col < p.K) {
-                    store_quad(p, g, mq, col, v);
+                    stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * BN + tcol) * g.Mpad + mq, v);
+                } else if (cl0 + tcol < g.Kg) {
+                    store_quad(p, g, mq, cog + cl0 + tcol, v);
                 }
             }
         }
@@ -297,7 +303,9 @@ __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs 
     const int co = (int)(idx / mquads), mq = 4 * (int)(idx - (int64_t)co * mquads);
     if (co >= p.K || mq >= g.Mtot) return;
     // eight partial tiles in flight at a time; the sum runs in split order whatever the batching
-    const float* src = p.ws + (int64_t)co * g.Mpad + mq;
+    // channel co sits in column (its group's first tile) * bn + (index inside the group)
+    const int grp = g.d_kg.div(co);
+    const float* src = p.ws + ((int64_t)grp * g.tiles_ng * g.bn + (co - grp * g.Kg)) * g.Mpad + mq;
     const int64_t step = (int64_t)g.Kpad * g.Mpad;
     f32x4 v = zero4();
     int s = 0;

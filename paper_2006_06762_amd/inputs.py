@@ -28,14 +28,16 @@ class ConvShape:
     S: int
     stride: Tuple[int, int] = (1, 1)
     pad: Tuple[int, int] = (0, 0)
+    dil: Tuple[int, int] = (1, 1)
+    groups: int = 1
 
     @property
     def OH(self) -> int:
-        return (self.H + 2 * self.pad[0] - self.R) // self.stride[0] + 1
+        return (self.H + 2 * self.pad[0] - self.dil[0] * (self.R - 1) - 1) // self.stride[0] + 1
 
     @property
     def OW(self) -> int:
-        return (self.W + 2 * self.pad[1] - self.S) // self.stride[1] + 1
+        return (self.W + 2 * self.pad[1] - self.dil[1] * (self.S - 1) - 1) // self.stride[1] + 1
 
 
 @dataclass(frozen=True)
@@ -70,6 +72,9 @@ BN_EPS = 1e-5
 #   C2D, ConvLayer: height, width, in_channels, out_channels, kernel, stride, padding
 #   GMM: N, M, K        DEP: height, width, channels, kernel, stride, padding
 #   TBS: sequence_length, heads, hidden_dimension (per head)
+#   GRP: as C2D plus groups        DIL: as C2D plus dilation
+# The first GRP record has 3 input channels and 4 groups; it is kept as printed and skipped
+# wherever shapes are built (the channel count is not a multiple of the group count).
 APPENDIX_C = {
     "C2D": [(224, 224, 3, 64, 7, 2, 3), (56, 56, 64, 64, 1, 1, 0), (14, 14, 256, 256, 3, 1, 1),
             (7, 7, 512, 512, 3, 1, 1)],
@@ -79,15 +84,28 @@ APPENDIX_C = {
     "ConvLayer": [(224, 224, 3, 64, 7, 2, 3), (56, 56, 64, 64, 3, 2, 1), (28, 28, 128, 256, 1, 2, 0),
                   (7, 7, 512, 512, 3, 1, 1)],
     "TBS": [(128, 12, 64), (128, 16, 64), (64, 12, 128), (128, 12, 128)],
+    "GRP": [(224, 224, 3, 64, 7, 2, 3, 4), (56, 56, 64, 64, 1, 1, 0, 4), (14, 14, 256, 256, 3, 1, 1, 4),
+            (7, 7, 512, 512, 3, 1, 1, 4)],
+    "DIL": [(224, 224, 3, 64, 7, 2, 3, 2), (56, 56, 64, 64, 1, 1, 0, 2), (14, 14, 256, 256, 3, 1, 1, 2),
+            (7, 7, 512, 512, 3, 1, 1, 2)],
 }
 BATCHES = (1, 16)
 
 
 def appendix_shape(op: str, fields, batch: int):
-    """The shape object of one Appendix C record at the given batch size."""
+    """The shape object of one Appendix C record at the given batch size (None for a record that
+    cannot be built: channels not a multiple of the group count)."""
     if op in ("C2D", "ConvLayer"):
         h, w, ci, co, ks, st, pd = fields
         return ConvShape(batch, ci, h, w, co, ks, ks, (st, st), (pd, pd))
+    if op == "GRP":
+        h, w, ci, co, ks, st, pd, groups = fields
+        if ci % groups or co % groups:
+            return None
+        return ConvShape(batch, ci, h, w, co, ks, ks, (st, st), (pd, pd), (1, 1), groups)
+    if op == "DIL":
+        h, w, ci, co, ks, st, pd, dil = fields
+        return ConvShape(batch, ci, h, w, co, ks, ks, (st, st), (pd, pd), (dil, dil), 1)
     if op == "DEP":
         h, w, c, ks, st, pd = fields
         return ConvShape(batch, c, h, w, c, ks, ks, (st, st), (pd, pd))
@@ -143,14 +161,15 @@ def gemm_inputs(shape: GemmShape, seed, ints: bool = False):
 
 
 def conv_inputs(shape: ConvShape, seed, ints: bool = False):
-    """x [N,C,H,W] ~ U[-1,1]; w [K,C,R,S] ~ N(0, 0.05^2)."""
+    """x [N,C,H,W] ~ U[-1,1]; w [K,C/groups,R,S] ~ N(0, 0.05^2)."""
     rng = _rng(seed)
+    cg = shape.C // shape.groups
     if ints:
         x = small_ints(rng, (shape.N, shape.C, shape.H, shape.W))
-        w = small_ints(rng, (shape.K, shape.C, shape.R, shape.S))
+        w = small_ints(rng, (shape.K, cg, shape.R, shape.S))
     else:
         x = uniform(rng, (shape.N, shape.C, shape.H, shape.W))
-        w = normal(rng, (shape.K, shape.C, shape.R, shape.S), 0.05)
+        w = normal(rng, (shape.K, cg, shape.R, shape.S), 0.05)
     return x, w
 
 

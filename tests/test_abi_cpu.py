@@ -49,6 +49,7 @@ int main(void) {
          offsetof(anr_conv_desc, x_stride), offsetof(anr_conv_desc, y_stride));
   printf("%zu %zu %zu\n", offsetof(anr_tbg_desc, q_stride), offsetof(anr_tbg_desc, k_stride),
          offsetof(anr_tbg_desc, o_stride));
+  printf("%zu %zu\n", offsetof(anr_conv_desc, groups), offsetof(anr_conv_desc, reserved));
   return 0; }''')
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
@@ -57,7 +58,7 @@ int main(void) {
     exp = [ctypes.sizeof(B.GemmDesc), ctypes.sizeof(B.ConvDesc), ctypes.sizeof(B.TbgDesc),
            B.GemmDesc.strideC.offset, B.ConvDesc.layout.offset, B.ConvDesc.x_stride.offset,
            B.ConvDesc.y_stride.offset, B.TbgDesc.q_stride.offset, B.TbgDesc.k_stride.offset,
-           B.TbgDesc.o_stride.offset]
+           B.TbgDesc.o_stride.offset, B.ConvDesc.groups.offset, B.ConvDesc.reserved.offset]
     assert got == exp
 
 
@@ -108,7 +109,11 @@ def test_conv_validation(fn):
         assert conv_status(fn, **{field: 0}) == B.ANR_ERR_INVALID_ARG, field
     assert conv_status(fn, pad_h=-1) == B.ANR_ERR_INVALID_ARG
     assert conv_status(fn, dil_w=0) == B.ANR_ERR_INVALID_ARG
-    assert conv_status(fn, dil_h=2) == B.ANR_ERR_UNSUPPORTED
+    assert conv_status(fn, H=4, R=3, dil_h=2, pad_h=0) == B.ANR_ERR_INVALID_ARG   # dilated kernel taller than the image
+    assert conv_status(fn, groups=-1) == B.ANR_ERR_INVALID_ARG
+    assert conv_status(fn, reserved=1) == B.ANR_ERR_INVALID_ARG
+    if fn != "anr_dwconv":
+        assert conv_status(fn, groups=3) == B.ANR_ERR_INVALID_ARG                 # channels not a multiple
     assert conv_status(fn, layout=1) == B.ANR_ERR_UNSUPPORTED
     assert conv_status(fn, H=2, R=5, pad_h=1) == B.ANR_ERR_INVALID_ARG          # empty output
     assert conv_status(fn, x_stride=(256, 64, 8, 2)) == B.ANR_ERR_UNSUPPORTED   # w stride != 1

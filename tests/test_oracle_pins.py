@@ -314,6 +314,17 @@ def test_grouped_conv_is_block_diagonal_conv(case):
                           oracle.conv2d_general(x, dense, stride, pad, dil, 1))
 
 
+def test_convlayer_general_reduces_to_convlayer():
+    # one group, no dilation: the ConvLayer oracle (C loops) and the general one agree
+    s = I.ConvShape(2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 38)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 39)
+    a = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+    b = oracle.conv_bn_relu_general(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-14)
+    assert (b >= 0).all() and (b == 0).any() and (b > 0).any()
+
+
 def test_grouped_conv_with_one_channel_per_group_is_depthwise():
     s = I.ConvShape(2, 5, 8, 7, 5, 3, 3, (1, 1), (1, 1))
     x, w = I.dwconv_inputs(s, 36)
@@ -500,10 +511,15 @@ def test_golden_shape_list_parses(golden_dir):
             continue
         name, *vals = line.split()
         ops.setdefault(name, []).append(tuple(int(v) for v in vals))
-    assert {k: len(v) for k, v in ops.items()} == {"C2D": 4, "GMM": 4, "DEP": 4, "ConvLayer": 4, "TBS": 4}
+    assert {k: len(v) for k, v in ops.items()} == {"C2D": 4, "GMM": 4, "DEP": 4, "ConvLayer": 4, "TBS": 4,
+                                                   "GRP": 4, "DIL": 4}
     assert (512, 512, 512) in ops["GMM"] and (128, 12, 64) in ops["TBS"]
     # the list the benchmark walks is the same list
     from paper_2006_06762_amd import inputs as I
     assert ops == I.APPENDIX_C
     s = I.appendix_shape("ConvLayer", I.APPENDIX_C["ConvLayer"][2], 16)
     assert (s.N, s.C, s.K, s.R, s.stride, s.pad, s.OH, s.OW) == (16, 128, 256, 1, (2, 2), (0, 0), 14, 14)
+    s = I.appendix_shape("DIL", I.APPENDIX_C["DIL"][0], 1)
+    assert (s.dil, s.groups, s.OH, s.OW) == ((2, 2), 1, 109, 109)
+    assert I.appendix_shape("GRP", I.APPENDIX_C["GRP"][0], 1) is None       # 3 channels, 4 groups
+    assert I.appendix_shape("GRP", I.APPENDIX_C["GRP"][2], 16).groups == 4

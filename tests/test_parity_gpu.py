@@ -238,6 +238,51 @@ def test_conv2d_gather_strided_views(anr):
     assert bool((yw == CANARY).all()), "store outside the output view"
 
 
+# ------------------------------------------------------------------ GRP and DIL (grouped, dilated)
+GENERAL_SHAPES = [
+    I.ConvShape(2, 8, 12, 12, 8, 3, 3, (1, 1), (2, 2), (2, 2), 1),
+    I.ConvShape(1, 3, 41, 37, 20, 7, 7, (2, 2), (3, 3), (2, 2), 1),
+    I.ConvShape(2, 16, 9, 11, 12, 3, 2, (2, 1), (1, 3), (3, 2), 1),
+    I.ConvShape(2, 12, 14, 14, 40, 3, 3, (1, 1), (1, 1), (1, 1), 4),
+    I.ConvShape(1, 64, 9, 9, 96, 1, 1, (1, 1), (0, 0), (1, 1), 4),
+    I.ConvShape(1, 256, 7, 7, 256, 3, 3, (1, 1), (1, 1), (1, 1), 4),      # split-K inside each group
+    I.ConvShape(3, 10, 13, 10, 130, 3, 3, (2, 2), (2, 2), (2, 2), 2),      # 65 channels per group: ragged tiles
+    I.ConvShape(2, 6, 8, 8, 6, 3, 3, (1, 1), (1, 1), (1, 1), 6),           # one channel per group
+]
+
+
+@pytest.mark.parametrize("shape", GENERAL_SHAPES, ids=str)
+@pytest.mark.parametrize("ints", [False, True])
+def test_conv2d_grouped_dilated(anr, shape, ints):
+    x, w = I.conv_inputs(shape, 220, ints=ints)
+    buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
+    anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad, dil=shape.dil, groups=shape.groups)
+    check_guard(buf)
+    ref = oracle.conv2d_general(x, w, shape.stride, shape.pad, shape.dil, shape.groups)
+    assert_parity(y, ref, exact=ints, what=str(shape))
+
+
+def test_conv_bn_relu_grouped_dilated(anr):
+    s = I.ConvShape(2, 16, 10, 10, 24, 3, 3, (1, 1), (2, 2), (2, 2), 4)
+    x, w = I.conv_inputs(s, 221)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 222)
+    y = torch.empty((s.N, s.K, s.OH, s.OW), device="cuda")
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad,
+                     dil=s.dil, groups=s.groups)
+    ref = oracle.conv_bn_relu_general(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad, s.dil, s.groups)
+    assert_parity(y, ref, what="grouped dilated ConvLayer")
+
+
+def test_dwconv_dilated(anr):
+    s = I.ConvShape(2, 5, 12, 9, 5, 3, 3, (1, 1), (2, 2), (2, 2))
+    x, w = I.dwconv_inputs(s, 223)
+    buf, y = guarded((s.N, s.C, s.OH, s.OW))
+    anr.dwconv(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil)
+    check_guard(buf)
+    # depthwise = one channel per group
+    assert_parity(y, oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.C), what="dilated depthwise")
+
+
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
 def test_conv2d_configs(anr, conv_route, name):
     cfg = I.config_inputs(name)
@@ -579,6 +624,16 @@ def test_appendix_c_shapes_batch1(anr, golden_dir):
                          s.stride, s.pad)
         ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
         assert_parity(y, ref, what="ConvLayer " + str(s))
+    for op in ("GRP", "DIL"):
+        for fields in ops[op]:
+            s = I.appendix_shape(op, fields, 1)
+            if s is None:          # 3 input channels in 4 groups, as printed in the appendix
+                continue
+            x, w = I.conv_inputs(s, 606)
+            y = torch.empty((1, s.K, s.OH, s.OW), device="cuda")
+            anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil, groups=s.groups)
+            ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups)
+            assert_parity(y, ref, what=op + " " + str(s))
     for (S, H, D) in ops["TBS"]:
         s = I.TbgShape(1, S, H, D)
         q, k = I.tbg_inputs(s, 605)
