@@ -50,6 +50,8 @@ def _load():
     lib.orc_conv_bn_relu.restype = None
     lib.orc_dwconv.argtypes = [_int] * 10 + [_f32p, _f32p, _f64p]
     lib.orc_dwconv.restype = None
+    lib.orc_nrm.argtypes = [_i64] * 5 + [_f32p, _f64p]
+    lib.orc_nrm.restype = None
     lib.orc_tbg.argtypes = [_int] * 4 + [_f32p, _f32p, _f64p]
     lib.orc_tbg.restype = _int
     lib.orc_tbs.argtypes = [_int] * 4 + [_f32p, _f32p, _f64p]
@@ -188,6 +190,17 @@ def dwconv(x, w, stride=(1, 1), pad=(0, 0)):
     _load().orc_dwconv(N, C, H, W, R, S, stride[0], stride[1], pad[0], pad[1],
                        _p32(x), _p32(w), _p64(y))
     return y
+
+
+def nrm(x):
+    """Entrywise 2-norm of each matrix: x [N,M] -> scalar array [1]; x [b,N,M] -> [b]."""
+    x = _f32(x)
+    if x.ndim == 2:
+        x = x[None]
+    b, N, M = x.shape
+    out = np.empty((b,), dtype=np.float64)
+    _load().orc_nrm(b, N, M, M, N * M, _p32(x), _p64(out))
+    return out
 
 
 def tbg(q, k):

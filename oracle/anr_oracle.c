@@ -230,6 +230,29 @@ void orc_dwconv(int N, int C, int H, int W, int R, int S,
 }
 
 /*
+ * NRM, Sec. 7.1 / Appendix C (fields: N, M): "matrix 2-norm", named in Sec. 4.1
+ * as the example of an operator with almost no parallelism in its space
+ * dimensions and ample parallelism in its reduction dimensions, i.e. a plain
+ * reduction over all entries of a matrix to one number.  Reading: the entrywise
+ * 2-norm  out[b] = sqrt(sum_{i,j} x[b,i,j]^2)  of each N x M matrix of the batch
+ * (row stride ld, matrix stride `stride`, in elements).
+ */
+void orc_nrm(int64_t batch, int64_t N, int64_t M, int64_t ld, int64_t stride,
+             const float *x, double *out)
+{
+    for (int64_t b = 0; b < batch; ++b) {
+        const float *xb = x + b * stride;
+        double acc = 0.0;
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t j = 0; j < M; ++j) {
+                const double v = xb[i * ld + j];
+                acc += v * v;
+            }
+        out[b] = sqrt(acc);
+    }
+}
+
+/*
  * TBS without its softmax ("TBG"), Sec. 7.2: two matrix transposes and one
  * batch matrix multiplication of multi-head attention.  q and k are
  * [B,S,H,D].  Step 1 and 2: materialise the transposed copies qt, kt =

@@ -491,6 +491,43 @@ def test_tbs_rows_are_softmax_of_tbg():
     assert np.array_equal(oracle.tbs(z, k), np.full_like(p, 1.0 / 6))
 
 
+# ---------------------------------------------------------------- NRM
+def test_nrm_vs_library_frobenius_norm():
+    # the entrywise 2-norm of a matrix is the Frobenius norm: numpy's routine on the same values
+    x = I.uniform(rng(51), (3, 37, 53))
+    ref = np.array([np.linalg.norm(x[b].astype(np.float64), "fro") for b in range(3)])
+    np.testing.assert_allclose(oracle.nrm(x), ref, rtol=1e-14)
+    np.testing.assert_allclose(oracle.nrm(x[1]), ref[1:2], rtol=1e-14)
+
+
+def test_nrm_closed_forms():
+    assert oracle.nrm(np.ones((6, 24), np.float32))[0] == 12.0                 # sqrt(N*M)
+    x = np.zeros((5, 7), np.float32)
+    x[3, 2] = -2.5
+    assert oracle.nrm(x)[0] == 2.5                                             # one entry: |a|, sign lost
+    x[0, 6] = 6.0
+    assert oracle.nrm(x)[0] == 6.5                                             # 2.5, 6, 6.5 triple
+    assert oracle.nrm(np.zeros((4, 4), np.float32))[0] == 0.0
+    # every entry counts once: an N x M ramp, sum of squares 1..n = n(n+1)(2n+1)/6
+    n = 12 * 9
+    ramp = np.arange(1, n + 1, dtype=np.float32).reshape(12, 9)
+    assert oracle.nrm(ramp)[0] == np.sqrt(n * (n + 1) * (2 * n + 1) / 6.0)
+
+
+def test_nrm_invariants():
+    x = I.uniform(rng(52), (2, 16, 10))
+    base = oracle.nrm(x)
+    # batch entries are independent; transposing or permuting entries changes nothing
+    np.testing.assert_allclose(oracle.nrm(np.ascontiguousarray(x.transpose(0, 2, 1))), base, rtol=1e-14)
+    np.testing.assert_allclose(oracle.nrm(x[::-1].copy()), base[::-1], rtol=0)
+    # homogeneity with an exactly representable factor
+    np.testing.assert_allclose(oracle.nrm((x * np.float32(-4.0))), 4.0 * base, rtol=1e-15)
+    # Pythagoras for matrices with disjoint supports
+    a = x.copy(); a[:, :, 5:] = 0
+    b = x.copy(); b[:, :, :5] = 0
+    np.testing.assert_allclose(np.sqrt(oracle.nrm(a) ** 2 + oracle.nrm(b) ** 2), base, rtol=1e-14)
+
+
 def test_oracle_thread_count_does_not_change_results():
     shape = I.ConvShape(2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1))
     x, w = I.conv_inputs(shape, 61)
