@@ -161,13 +161,19 @@ def shape_list(anr, I, torch):
     rnd = lambda *shape: torch.rand(shape, generator=gen, device="cuda", dtype=torch.float32) * 2 - 1
     emp = lambda *shape: torch.empty(shape, device="cuda", dtype=torch.float32)
     rows = []
-    for op in ("GMM", "C2D", "DEP", "ConvLayer", "TBS", "GRP", "DIL"):
+    for op in ("GMM", "C2D", "DEP", "ConvLayer", "TBS", "GRP", "DIL", "NRM"):
         for fields in I.APPENDIX_C[op]:
             for batch in I.BATCHES:
-                s = I.appendix_shape(op, fields, batch)
+                s = I.appendix_shape(op, fields, batch) if op != "NRM" else fields
                 if s is None:          # a record that cannot be built (3 channels in 4 groups)
                     continue
-                if op == "GMM":
+                if op == "NRM":
+                    n_, m_ = fields
+                    flops = 2.0 * batch * n_ * m_
+                    nbytes = 4.0 * batch * n_ * m_
+                    mk = lambda: (rnd(batch, n_, m_), emp(batch))
+                    run = lambda t: anr.nrm(t[0], t[1])
+                elif op == "GMM":
                     flops = 2.0 * s.batch * s.M * s.N * s.K
                     nbytes = 4.0 * s.batch * (s.M * s.K + s.K * s.N + s.M * s.N)
                     mk = lambda: (rnd(s.batch, s.M, s.K), rnd(s.batch, s.K, s.N), emp(s.batch, s.M, s.N))

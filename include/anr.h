@@ -56,7 +56,7 @@ typedef enum { ANR_LAYOUT_NCHW = 0 } anr_layout;
 
 typedef enum {
     ANR_OP_GEMM = 0, ANR_OP_CONV2D = 1, ANR_OP_CONV_BN_RELU = 2, ANR_OP_DWCONV = 3,
-    ANR_OP_TBG = 4, ANR_OP_TBS = 5
+    ANR_OP_TBG = 4, ANR_OP_TBS = 5, ANR_OP_NRM = 6
 } anr_op;
 
 /*
@@ -161,6 +161,24 @@ anr_status anr_tbg(const anr_tbg_desc *desc, const float *q, const float *k, flo
  * anr_tbg kernel and an in-place softmax kernel on the same stream.
  * Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
 anr_status anr_tbs(const anr_tbg_desc *desc, const float *q, const float *k, float *out,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * NRM.  N x M row-major matrices, row stride ld >= M, matrix b at x + b*stride
+ * (stride >= (N-1)*ld + M for batch > 1, or 0 to reduce one matrix `batch`
+ * times); batch <= 65535.
+ */
+typedef struct {
+    int64_t N, M, ld;
+    int64_t batch, stride;
+} anr_nrm_desc;
+
+/* NRM (Sec. 7.1, Appendix C "NRM"; Sec. 4.1 names it as the operator with
+ * parallelism only in its reduction): out[b] = sqrt(sum_{i,j} x[b,i,j]^2),
+ * `batch` device floats.  Matrices of more than 16 K elements are reduced in
+ * slices whose partial sums pass through `ws` (anr_workspace_size); the sum
+ * order is fixed, so results do not vary from run to run. */
+anr_status anr_nrm(const anr_nrm_desc *desc, const float *x, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Bytes of device workspace `op` (an anr_op) may want for `desc` (the matching

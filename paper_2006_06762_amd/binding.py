@@ -25,9 +25,9 @@ _lib = ctypes.CDLL(LIB_PATH)
 
 ANR_OK, ANR_ERR_NULL, ANR_ERR_INVALID_ARG, ANR_ERR_UNSUPPORTED, ANR_ERR_WORKSPACE, ANR_ERR_LAUNCH = range(6)
 ANR_LAYOUT_NCHW = 0
-ANR_OP_GEMM, ANR_OP_CONV2D, ANR_OP_CONV_BN_RELU, ANR_OP_DWCONV, ANR_OP_TBG, ANR_OP_TBS = range(6)
+ANR_OP_GEMM, ANR_OP_CONV2D, ANR_OP_CONV_BN_RELU, ANR_OP_DWCONV, ANR_OP_TBG, ANR_OP_TBS, ANR_OP_NRM = range(7)
 
-EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
+EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
            "anr_workspace_size", "anr_status_string", "anr_version", "anr_last_hip_error",
            "anr_last_hip_error_string")
 
@@ -50,6 +50,11 @@ class ConvDesc(ctypes.Structure):
                 ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
+class NrmDesc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("M", ctypes.c_int64), ("ld", ctypes.c_int64),
+                ("batch", ctypes.c_int64), ("stride", ctypes.c_int64)]
+
+
 class TbgDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("S", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("q_stride", ctypes.c_int64 * 4), ("k_stride", ctypes.c_int64 * 4),
@@ -64,6 +69,7 @@ _lib.anr_conv_bn_relu.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, 
 _lib.anr_dwconv.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_tbg.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_tbs.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.anr_nrm.argtypes = [ctypes.POINTER(NrmDesc), _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_workspace_size.argtypes = [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_size_t)]
 for _name in ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
               "anr_workspace_size"):
@@ -241,4 +247,19 @@ def tbs(q, k, out):
     """tbg followed by a softmax over the last axis."""
     d = _tbg_desc(q, k, out)
     _check(_lib.anr_tbs(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(out), None, 0, _stream()), "anr_tbs")
+    return out
+
+
+def nrm(x, out, ws=None):
+    """out[b] = sqrt(sum of squares of x[b]).  x [N,M] or [b,N,M] with unit column stride, out [1] / [b]."""
+    if x.dim() == 2:
+        N, M = x.shape
+        d = NrmDesc(N, M, x.stride(0), 1, 0)
+    else:
+        b, N, M = x.shape
+        d = NrmDesc(N, M, x.stride(1), b, x.stride(0) if b > 1 else 0)
+    if x.stride(-1) != 1 or not out.is_contiguous() or out.numel() != d.batch:
+        raise ValueError("x needs unit column stride and out one packed float per matrix")
+    wp, wb = _workspace(ANR_OP_NRM, d, ws)
+    _check(_lib.anr_nrm(ctypes.byref(d), _ptr(x), _ptr(out), wp, wb, _stream()), "anr_nrm")
     return out

@@ -74,4 +74,16 @@ size_t conv2d_workspace_bytes(const ConvArgs& a);
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream);
 hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
 
+// out[b] = sqrt(sum of squares of the N x M matrix b); rows `ld` apart, matrices `stride` apart.
+struct NrmArgs {
+    const float* x;
+    float* out;
+    int64_t N, M, ld, stride;
+    int batch;           // <= 65535
+    float* ws;           // partial sums of the slices (see nrm_workspace_bytes)
+    size_t ws_bytes;
+};
+size_t nrm_workspace_bytes(const NrmArgs& a);
+hipError_t launch_nrm(const NrmArgs& a, hipStream_t stream);
+
 }  // namespace anr

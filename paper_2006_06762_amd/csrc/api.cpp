@@ -176,6 +176,17 @@ anr_status run_tbg(const anr_tbg_desc* d, const float* q, const float* k, float*
     return launch_status(anr::launch_tbg(a, static_cast<hipStream_t>(hip_stream)));
 }
 
+anr_status check_nrm(const anr_nrm_desc* d, anr::NrmArgs* a)
+{
+    if (!d) return ANR_ERR_NULL;
+    if (d->N < 1 || d->M < 1 || d->batch < 1 || d->ld < d->M || d->stride < 0) return ANR_ERR_INVALID_ARG;
+    if (d->batch > 65535) return ANR_ERR_UNSUPPORTED;
+    if (d->N >= ((int64_t)1 << 31) || d->M >= ((int64_t)1 << 31)) return ANR_ERR_UNSUPPORTED;
+    a->N = d->N; a->M = d->M; a->ld = d->ld; a->stride = d->stride;
+    a->batch = (int)d->batch;
+    return ANR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -254,12 +265,32 @@ anr_status anr_tbs(const anr_tbg_desc* d, const float* q, const float* k, float*
     return run_tbg(d, q, k, out, true, hip_stream);
 }
 
+anr_status anr_nrm(const anr_nrm_desc* d, const float* x, float* out, void* ws, size_t ws_bytes,
+                   void* hip_stream)
+{
+    anr::NrmArgs a{};
+    anr_status st = check_nrm(d, &a);
+    if (st != ANR_OK) return st;
+    if (!x || !out) return ANR_ERR_NULL;
+    a.x = x;
+    a.out = out;
+    const size_t need = anr::nrm_workspace_bytes(a);
+    if (need > 0) {
+        if (!ws || ws_bytes < need) return ANR_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(ws) & 3) return ANR_ERR_INVALID_ARG;
+        a.ws = static_cast<float*>(ws);
+        a.ws_bytes = ws_bytes;
+    }
+    return launch_status(anr::launch_nrm(a, static_cast<hipStream_t>(hip_stream)));
+}
+
 anr_status anr_workspace_size(int op, const void* desc, size_t* bytes)
 {
     if (!desc || !bytes) return ANR_ERR_NULL;
     anr_status st;
     ConvGeom cg;
     TbgGeom tg;
+    anr::NrmArgs na{};
     switch (op) {
         case ANR_OP_GEMM: st = check_gemm(static_cast<const anr_gemm_desc*>(desc)); break;
         case ANR_OP_CONV2D:
@@ -267,10 +298,12 @@ anr_status anr_workspace_size(int op, const void* desc, size_t* bytes)
         case ANR_OP_DWCONV: st = check_conv(static_cast<const anr_conv_desc*>(desc), true, &cg); break;
         case ANR_OP_TBG: st = check_tbg(static_cast<const anr_tbg_desc*>(desc), false, &tg); break;
         case ANR_OP_TBS: st = check_tbg(static_cast<const anr_tbg_desc*>(desc), true, &tg); break;
+        case ANR_OP_NRM: st = check_nrm(static_cast<const anr_nrm_desc*>(desc), &na); break;
         default: return ANR_ERR_INVALID_ARG;
     }
     if (st != ANR_OK) return st;
     *bytes = 0;
+    if (op == ANR_OP_NRM) *bytes = anr::nrm_workspace_bytes(na);
     if (op == ANR_OP_CONV2D || op == ANR_OP_CONV_BN_RELU) {
         // an upper bound that does not depend on pointer alignment: what the general kernel's
         // split-K needs for this shape (the tuned kernel, when it takes the call, needs none)

@@ -72,7 +72,7 @@ BN_EPS = 1e-5
 #   C2D, ConvLayer: height, width, in_channels, out_channels, kernel, stride, padding
 #   GMM: N, M, K        DEP: height, width, channels, kernel, stride, padding
 #   TBS: sequence_length, heads, hidden_dimension (per head)
-#   GRP: as C2D plus groups        DIL: as C2D plus dilation
+#   GRP: as C2D plus groups        DIL: as C2D plus dilation        NRM: N, M
 # The first GRP record has 3 input channels and 4 groups; it is kept as printed and skipped
 # wherever shapes are built (the channel count is not a multiple of the group count).
 APPENDIX_C = {
@@ -86,6 +86,7 @@ APPENDIX_C = {
     "TBS": [(128, 12, 64), (128, 16, 64), (64, 12, 128), (128, 12, 128)],
     "GRP": [(224, 224, 3, 64, 7, 2, 3, 4), (56, 56, 64, 64, 1, 1, 0, 4), (14, 14, 256, 256, 3, 1, 1, 4),
             (7, 7, 512, 512, 3, 1, 1, 4)],
+    "NRM": [(256, 256), (512, 512), (1024, 1024), (4096, 4096)],
     "DIL": [(224, 224, 3, 64, 7, 2, 3, 2), (56, 56, 64, 64, 1, 1, 0, 2), (14, 14, 256, 256, 3, 1, 1, 2),
             (7, 7, 512, 512, 3, 1, 1, 2)],
 }

@@ -161,6 +161,24 @@ def test_tbg_validation(fn):
         assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
 
 
+def test_nrm_validation():
+    lib = B.raw()
+    ok = dict(N=8, M=8, ld=8, batch=1, stride=0)
+    for field, bad in (("N", 0), ("M", 0), ("batch", 0), ("ld", 7), ("stride", -1)):
+        d = B.NrmDesc(**dict(ok, **{field: bad}))
+        assert lib.anr_nrm(ctypes.byref(d), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG, field
+    d = B.NrmDesc(**ok)
+    assert lib.anr_nrm(None, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_nrm(ctypes.byref(d), None, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_nrm(ctypes.byref(d), DUMMY, None, None, 0, None) == B.ANR_ERR_NULL
+    assert lib.anr_nrm(ctypes.byref(B.NrmDesc(8, 8, 8, 70000, 64)), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
+    assert B.workspace_size(B.ANR_OP_NRM, d) == 0                      # one slice: no partial sums
+    big = B.NrmDesc(4096, 4096, 4096, 1, 0)
+    need = B.workspace_size(B.ANR_OP_NRM, big)
+    assert need == 4 * 1024                                             # 16 M elements in 1024 slices
+    assert lib.anr_nrm(ctypes.byref(big), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_WORKSPACE
+
+
 def test_workspace_size():
     g = B.GemmDesc(512, 512, 512, 512, 512, 512, 1, 0, 0, 0)
     assert B.workspace_size(B.ANR_OP_GEMM, g) == 0

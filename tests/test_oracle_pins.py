@@ -549,7 +549,7 @@ def test_golden_shape_list_parses(golden_dir):
         name, *vals = line.split()
         ops.setdefault(name, []).append(tuple(int(v) for v in vals))
     assert {k: len(v) for k, v in ops.items()} == {"C2D": 4, "GMM": 4, "DEP": 4, "ConvLayer": 4, "TBS": 4,
-                                                   "GRP": 4, "DIL": 4}
+                                                   "GRP": 4, "DIL": 4, "NRM": 4}
     assert (512, 512, 512) in ops["GMM"] and (128, 12, 64) in ops["TBS"]
     # the list the benchmark walks is the same list
     from paper_2006_06762_amd import inputs as I

@@ -583,6 +583,39 @@ def test_tbs_config_shape(anr):
     assert_softmax_parity(out, oracle.tbs(cfg["q"], cfg["k"]), what="TBS config")
 
 
+# ------------------------------------------------------------------ NRM
+NRM_TOL = 2e-6      # relative: fp32 partial sums of at most a few thousand squares each, then a tree
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (1, 33, 7), (1, 256, 256), (3, 100, 37), (16, 512, 512),
+                                   (1, 1000, 1000), (2, 2048, 1024), (1, 4096, 4096)], ids=str)
+def test_nrm(anr, shape):
+    b, N, M = shape
+    x = I.uniform(np.random.Generator(np.random.PCG64(700 + N)), (b, N, M))
+    out = torch.full((b + 2,), CANARY, device="cuda")
+    anr.nrm(dev(x) if b > 1 else dev(x[0]), out[1:1 + b])
+    ref = oracle.nrm(x)
+    got = out.cpu().numpy().astype(np.float64)
+    assert got[0] == CANARY and got[-1] == CANARY
+    assert float(np.max(np.abs(got[1:-1] - ref) / ref)) <= NRM_TOL
+    assert_parity(out[1:1 + b], ref, what="nrm %s" % (shape,))
+
+
+def test_nrm_strided_rows_and_exact_small_integers(anr):
+    # a view into a wider matrix (row stride > M, unaligned start) takes the element-wise path;
+    # small integers: the sum of squares is exact in fp32, so the result is the rounded root
+    x = I.small_ints(np.random.Generator(np.random.PCG64(710)), (2, 50, 30))
+    wide = torch.zeros((2, 50, 41), device="cuda")
+    wide[:, :, 3:33] = dev(x)
+    out = torch.empty((2,), device="cuda")
+    anr.nrm(wide[:, :, 3:33], out)
+    ref = oracle.nrm(x)
+    assert np.array_equal(out.cpu().numpy(), ref.astype(np.float32))
+    out2 = torch.empty((2,), device="cuda")
+    anr.nrm(dev(x), out2)
+    assert torch.equal(out, out2)
+
+
 # ------------------------------------------------------------------ paper shape lists (Appendix C)
 def appendix_c(golden_dir):
     import os
@@ -624,6 +657,12 @@ def test_appendix_c_shapes_batch1(anr, golden_dir):
                          s.stride, s.pad)
         ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
         assert_parity(y, ref, what="ConvLayer " + str(s))
+    for (n, m) in ops["NRM"]:
+        x = I.uniform(np.random.Generator(np.random.PCG64(607)), (n, m))
+        out = torch.empty((1,), device="cuda")
+        anr.nrm(dev(x), out)
+        ref = oracle.nrm(x)
+        assert abs(float(out[0]) - ref[0]) / ref[0] <= NRM_TOL, "NRM %s" % ((n, m),)
     for op in ("GRP", "DIL"):
         for fields in ops[op]:
             s = I.appendix_shape(op, fields, 1)
