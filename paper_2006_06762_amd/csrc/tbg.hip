@@ -11,6 +11,8 @@ hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipS
     tbg::Args t = t0;
     const int rows_q = 32 * QB, ld = t.D + 4;
     t.tiles_i = (t.S + rows_q - 1) / rows_q;
+    const int64_t items = (int64_t)batch * t.tiles_i;
+    t.xcd_chunk = (items % 8 == 0) ? (int)(items / 8) : 0;
     // q rows, then the k panel, which the staged probabilities (rows_q x kLdP) later overwrite
     const size_t kpanel = (size_t)tbg::kRowsKeys * ld, probs = (size_t)rows_q * tbg::kLdP;
     const size_t lds_bytes = sizeof(float) * ((size_t)rows_q * ld + (kpanel > probs ? kpanel : probs));
