@@ -5,25 +5,36 @@
 namespace anr {
 namespace {
 
-template <int UT, int QB>
+template <int UT, int KB>
 hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipStream_t stream)
 {
+    using T = tbg::TbsShape<KB>;
     tbg::Args t = t0;
-    const int rows_q = 32 * QB, ld = t.D + 4;
-    t.tiles_i = (t.S + rows_q - 1) / rows_q;
+    const int ld = t.D + 4;
+    t.tiles_i = (t.S + T::rows_q - 1) / T::rows_q;
     const int64_t items = (int64_t)batch * t.tiles_i;
     t.xcd_chunk = (items % 8 == 0) ? (int)(items / 8) : 0;
-    // q rows, then the k panel, which the staged probabilities (rows_q x kLdP) later overwrite
-    const size_t kpanel = (size_t)tbg::kRowsKeys * ld, probs = (size_t)rows_q * tbg::kLdP;
-    const size_t lds_bytes = sizeof(float) * ((size_t)rows_q * ld + (kpanel > probs ? kpanel : probs));
-    auto kern = tbg::tbs_rows32_kernel<UT, true, QB>;
+    // q rows, then the k panel, which the staged probabilities (rows_q x ldp) later overwrite
+    const size_t kpanel = (size_t)T::rows_k * ld, probs = (size_t)T::rows_q * T::ldp;
+    const size_t lds_bytes = sizeof(float) * ((size_t)T::rows_q * ld + (kpanel > probs ? kpanel : probs));
+    auto kern = tbg::tbs_rows32_kernel<UT, true, KB>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return launch_kernel(kern, dim3((unsigned)(batch * t.tiles_i)), dim3(256 * QB), lds_bytes, stream, t, ld,
-                         vec_store);
+    return launch_kernel(kern, dim3((unsigned)items), dim3(256), lds_bytes, stream, t, ld, vec_store);
+}
+
+// UT for D <= 32 / 64 / 128 is (rows_q + rows_k) * (D/4) / 256 rounded up: 160 rows for KB = 4
+// and 1, 128 rows for KB = 2.
+template <int KB>
+hipError_t launch_tbs_by_d(const tbg::Args& t, int batch, int vec_store, hipStream_t stream)
+{
+    constexpr int rows = tbg::TbsShape<KB>::rows_q + tbg::TbsShape<KB>::rows_k;
+    if (t.D <= 32) return launch_tbs_rows32<(rows * 8 + 255) / 256, KB>(t, batch, vec_store, stream);
+    if (t.D <= 64) return launch_tbs_rows32<(rows * 16 + 255) / 256, KB>(t, batch, vec_store, stream);
+    return launch_tbs_rows32<(rows * 32 + 255) / 256, KB>(t, batch, vec_store, stream);
 }
 
 }  // namespace
@@ -48,12 +59,12 @@ hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream)
     t.os_b = a.sCo; t.os_h = a.sCi; t.os_i = a.ldc;
     t.tiles_i = tiles; t.tiles_j = tiles;
     t.xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
-    if (a.softmax_rows && a.M <= tbg::kRowsKeys && a.K <= 128 && (a.K % 8 == 0)) {
-        // fused TBS: 32 query rows x all keys per work-group
+    if (a.softmax_rows && a.M <= tbg::kMaxKeys && a.K <= 128 && (a.K % 8 == 0)) {
+        // fused TBS: a block of query rows x all keys per work-group
         const int vec_store = is_aligned16(a.C) && (a.ldc % 4 == 0) && (a.sCo % 4 == 0) && (a.sCi % 4 == 0);
-        if (a.K <= 32) return launch_tbs_rows32<5, 1>(t, a.batch, vec_store, stream);
-        if (a.K <= 64) return launch_tbs_rows32<10, 1>(t, a.batch, vec_store, stream);
-        return launch_tbs_rows32<20, 1>(t, a.batch, vec_store, stream);
+        if (a.M <= 32) return launch_tbs_by_d<1>(t, a.batch, vec_store, stream);
+        if (a.M <= 64) return launch_tbs_by_d<2>(t, a.batch, vec_store, stream);
+        return launch_tbs_by_d<4>(t, a.batch, vec_store, stream);
     }
     hipError_t err = launch_kernel(tbg::tbg_tile_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t);
     if (err != hipSuccess || !a.softmax_rows) return err;

@@ -141,8 +141,9 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
 // transposes, one batch matmul, one softmax), so a row of scores never leaves the chip
 // before it is normalised.
 //
-// Work-group = 32 queries x ALL keys of one (b, h); wave w owns keys 32w .. 32w + 31.  The
-// benchmark shape gives 768 work-groups = 3 per CU, 3 waves on every SIMD.  The q rows and
+// Work-group = a block of queries x ALL keys of one (b, h); a wave owns 32 keys.  The benchmark
+// shape (S = 128: 32 queries per work-group, wave w owns keys 32w .. 32w + 31) gives 768
+// work-groups = 3 per CU, 3 waves on every SIMD.  The q rows and
 // the k panel are staged in LDS with fully coalesced 16-byte loads (loading the MFMA operand
 // registers straight from global memory was measured at 14.3 us for the matmul alone: a lane
 // is a matrix row there, so every request touches 32 cache lines for 32 bytes each).
@@ -154,24 +155,34 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
 // probabilities go back through LDS (over the k panel) so that each store instruction writes
 // two complete output rows.
 //
-// UT = 16-byte staging units per thread: ceil(160 * (D/4) / 256).
-constexpr int kRowsKeys = 128;
-constexpr int kLdP = kRowsKeys + 4;       // row stride of the staged probabilities
+// The four waves are KB key blocks x 4/KB query blocks of 32: KB = 4 for S <= 128 (32 queries
+// per work-group), 2 for S <= 64 (64 queries), 1 for S <= 32 (128 queries), so a short sequence
+// neither loads nor multiplies key rows it does not have.
+// UT = 16-byte staging units per thread: ceil((32 * 4/KB + 32 * KB) * (D/4) / 256).
+constexpr int kMaxKeys = 128;
 
-template <int UT, bool SOFTMAX, int QB>
-__global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int ld, int vec_store)
+template <int KB>
+struct TbsShape {
+    static constexpr int QBK = 4 / KB;            // query blocks per work-group
+    static constexpr int rows_q = 32 * QBK, rows_k = 32 * KB;
+    static constexpr int ldp = rows_k + 4;        // row stride of the staged probabilities
+};
+
+template <int UT, bool SOFTMAX, int KB>
+__global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, int vec_store)
 {
-    extern __shared__ __attribute__((aligned(16))) float panel[];   // q rows 0..31, then k rows 0..127
-    constexpr int kRowsQ = 32 * QB, NT = 256 * QB;
-    __shared__ float red[2][QB][4][32];
+    using T = TbsShape<KB>;
+    constexpr int QBK = T::QBK, kRowsQ = T::rows_q, kRowsK = T::rows_k, kLdP = T::ldp;
+    extern __shared__ __attribute__((aligned(16))) float panel[];   // q rows, then k rows
+    __shared__ float red[2][QBK][KB][32];
     float* const qs = panel;
     float* const ks = panel + kRowsQ * ld;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
-    const int wave = wv & 3, qblk = wv >> 2;    // key block, query block
+    const int wave = wv % KB, qblk = wv / KB;   // key block, query block
     const int r32 = lane & 31, h2 = lane >> 5;
-    // work item = (b*H + h) * tiles_i + ti, tiles_i = ceil(S / 32).  Work-group ids are dealt
+    // work item = (b*H + h) * tiles_i + ti, tiles_i = ceil(S / rows_q).  Work-group ids are dealt
     // round-robin over the 8 XCDs; every XCD gets a contiguous range of items, so that the query
     // tiles of one head, which all read its k panel, meet in one L2 (31.6 -> 12.7 MB fetched).
     int item = blockIdx.x;
@@ -184,11 +195,11 @@ __global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int 
     const float* __restrict__ qb = p.q + b * p.qs_b + hh * p.qs_h;
     const float* __restrict__ kb = p.k + b * p.ks_b + hh * p.ks_h;
 
-    // staging unit u of thread tid: unit index tid + 256*u of the 160 x (D/4) panel, walked
-    // without a division per unit
+    // staging unit u of thread tid: unit index tid + 256*u of the (rows_q + rows_k) x (D/4) panel,
+    // walked without a division per unit
     const int dq = p.D >> 2;
-    const int row_step = NT / dq, col_step = NT - row_step * dq;
-    const int rows_all = kRowsQ + kRowsKeys;
+    const int row_step = 256 / dq, col_step = 256 - row_step * dq;
+    constexpr int rows_all = kRowsQ + kRowsK;
     int srow = tid / dq, scol = tid - srow * dq;
     f32x4 rg[UT];
     int lds_off[UT];
@@ -239,8 +250,10 @@ __global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int 
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         if (h2 == 0) red[0][qblk][wave][r32] = mx;
         __syncthreads();
-        // key 0 is always inside, so the maximum over the four key blocks is finite
-        mx = fmaxf(fmaxf(red[0][qblk][0][r32], red[0][qblk][1][r32]), fmaxf(red[0][qblk][2][r32], red[0][qblk][3][r32]));
+        // key 0 is always inside, so the maximum over the key blocks is finite
+        mx = red[0][qblk][0][r32];
+#pragma unroll
+        for (int w = 1; w < KB; ++w) mx = fmaxf(mx, red[0][qblk][w][r32]);
         float sum = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -250,7 +263,9 @@ __global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int 
         sum += __shfl_xor(sum, 32);
         if (h2 == 0) red[1][qblk][wave][r32] = sum;
         __syncthreads();
-        sum = (red[1][qblk][0][r32] + red[1][qblk][1][r32]) + (red[1][qblk][2][r32] + red[1][qblk][3][r32]);
+        sum = red[1][qblk][0][r32];
+#pragma unroll
+        for (int w = 1; w < KB; ++w) sum += red[1][qblk][w][r32];
         const float inv = 1.0f / sum;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] *= inv;
@@ -267,11 +282,14 @@ __global__ __launch_bounds__(256 * QB) void tbs_rows32_kernel(const Args p, int 
         *reinterpret_cast<f32x4*>(&ps[(32 * qblk + r32) * kLdP + key0 + 8 * g]) = v;
     }
     __syncthreads();
+    // 8*KB lanes cover one row of 32*KB probabilities with 16 bytes each; a store instruction
+    // writes 8/KB whole rows, every wave 8*QBK rows in four instructions
     float* __restrict__ ob = p.out + b * p.os_b + hh * p.os_h;
-    const int col = 4 * r32;
+    constexpr int LPR = 8 * KB, RPI = 64 / LPR;
+    const int col = 4 * (lane % LPR);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int rl = 8 * wv + 2 * i + h2;
+        const int rl = 8 * QBK * wv + RPI * i + lane / LPR;
         const int row = i0 + rl;
         const f32x4 v = *reinterpret_cast<const f32x4*>(&ps[rl * kLdP + col]);
         if (row < p.S) {

@@ -534,7 +534,10 @@ def assert_softmax_parity(got_t, ref, what=""):
 TBS_SHAPES = [I.TbgShape(2, 5, 3, 4), I.TbgShape(1, 128, 2, 64), I.TbgShape(1, 130, 2, 33),
               I.TbgShape(2, 64, 12, 128), I.TbgShape(1, 1, 1, 8), I.TbgShape(3, 65, 2, 8),
               I.TbgShape(1, 100, 5, 32), I.TbgShape(2, 96, 3, 24), I.TbgShape(1, 128, 3, 128),
-              I.TbgShape(1, 127, 2, 72), I.TbgShape(1, 129, 2, 64), I.TbgShape(1, 33, 2, 136)]
+              I.TbgShape(1, 127, 2, 72), I.TbgShape(1, 129, 2, 64), I.TbgShape(1, 33, 2, 136),
+              # short sequences: two key blocks x two query blocks, one key block x four query blocks
+              I.TbgShape(2, 64, 3, 64), I.TbgShape(1, 48, 5, 40), I.TbgShape(2, 32, 3, 128),
+              I.TbgShape(3, 20, 2, 16), I.TbgShape(1, 33, 2, 8)]
 
 
 @pytest.mark.parametrize("shape", TBS_SHAPES, ids=str)
