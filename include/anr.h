@@ -157,7 +157,7 @@ anr_status anr_tbg(const anr_tbg_desc *desc, const float *q, const float *k, flo
 
 /* Full TBS (Sec. 7.2, Appendix C "TBS"): the scores of anr_tbg followed by a
  * softmax over j (max-subtracted): out[b,h,i,:] = softmax_j(sum_d q.k).  One
- * fused kernel when S <= 128 and D is a multiple of 8 up to 128; otherwise the
+ * fused kernel when S <= 128 and D is a multiple of 8 up to 1024; otherwise the
  * anr_tbg kernel and an in-place softmax kernel on the same stream.
  * Requires S <= 1024 (else ANR_ERR_UNSUPPORTED). */
 anr_status anr_tbs(const anr_tbg_desc *desc, const float *q, const float *k, float *out,

@@ -10,7 +10,7 @@ hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipS
 {
     using T = tbg::TbsShape<KB>;
     tbg::Args t = t0;
-    const int ld = t.D + 4;
+    const int ld = (t.D < tbg::kChunk ? t.D : tbg::kChunk) + 4;     // the panel in LDS is one chunk wide
     t.tiles_i = (t.S + T::rows_q - 1) / T::rows_q;
     const int64_t items = (int64_t)batch * t.tiles_i;
     t.xcd_chunk = (items % 8 == 0) ? (int)(items / 8) : 0;
@@ -26,15 +26,14 @@ hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipS
     return launch_kernel(kern, dim3((unsigned)items), dim3(256), lds_bytes, stream, t, ld, vec_store);
 }
 
-// UT for D <= 32 / 64 / 128 is (rows_q + rows_k) * (D/4) / 256 rounded up: 160 rows for KB = 4
-// and 1, 128 rows for KB = 2.
+// UT for D <= 32 / more is (rows_q + rows_k) * (chunk/4) / 256 rounded up: 160 rows for KB = 4
+// and 1, 128 rows for KB = 2; the chunk is at most 64 columns.
 template <int KB>
 hipError_t launch_tbs_by_d(const tbg::Args& t, int batch, int vec_store, hipStream_t stream)
 {
     constexpr int rows = tbg::TbsShape<KB>::rows_q + tbg::TbsShape<KB>::rows_k;
     if (t.D <= 32) return launch_tbs_rows32<(rows * 8 + 255) / 256, KB>(t, batch, vec_store, stream);
-    if (t.D <= 64) return launch_tbs_rows32<(rows * 16 + 255) / 256, KB>(t, batch, vec_store, stream);
-    return launch_tbs_rows32<(rows * 32 + 255) / 256, KB>(t, batch, vec_store, stream);
+    return launch_tbs_rows32<(rows * 16 + 255) / 256, KB>(t, batch, vec_store, stream);
 }
 
 }  // namespace
@@ -59,7 +58,7 @@ hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream)
     t.os_b = a.sCo; t.os_h = a.sCi; t.os_i = a.ldc;
     t.tiles_i = tiles; t.tiles_j = tiles;
     t.xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
-    if (a.softmax_rows && a.M <= tbg::kMaxKeys && a.K <= 128 && (a.K % 8 == 0)) {
+    if (a.softmax_rows && a.M <= tbg::kMaxKeys && a.K <= 1024 && (a.K % 8 == 0)) {
         // fused TBS: a block of query rows x all keys per work-group
         const int vec_store = is_aligned16(a.C) && (a.ldc % 4 == 0) && (a.sCo % 4 == 0) && (a.sCi % 4 == 0);
         if (a.M <= 32) return launch_tbs_by_d<1>(t, a.batch, vec_store, stream);

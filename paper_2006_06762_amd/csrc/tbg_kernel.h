@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
 // The four waves are KB key blocks x 4/KB query blocks of 32: KB = 4 for S <= 128 (32 queries
 // per work-group), 2 for S <= 64 (64 queries), 1 for S <= 32 (128 queries), so a short sequence
 // neither loads nor multiplies key rows it does not have.
-// UT = 16-byte staging units per thread: ceil((32 * 4/KB + 32 * KB) * (D/4) / 256).
+// UT = 16-byte staging units per thread: ceil((32 * 4/KB + 32 * KB) * (min(D, 64)/4) / 256).
 constexpr int kMaxKeys = 128;
 
 template <int KB>
@@ -195,14 +195,18 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     const float* __restrict__ qb = p.q + b * p.qs_b + hh * p.qs_h;
     const float* __restrict__ kb = p.k + b * p.ks_b + hh * p.ks_h;
 
-    // staging unit u of thread tid: unit index tid + 256*u of the (rows_q + rows_k) x (D/4) panel,
-    // walked without a division per unit
-    const int dq = p.D >> 2;
+    // The reduction runs in chunks of 64 columns of d (the panel in LDS is 64 wide, so three
+    // work-groups fit a CU for any D); the next chunk waits in registers while this one is
+    // multiplied.  Staging unit u of thread tid: unit index tid + 256*u of the
+    // (rows_q + rows_k) x (chunk/4) panel, walked without a division per unit.
+    const int dc = p.D < kChunk ? p.D : kChunk;
+    const int dq = dc >> 2;
     const int row_step = 256 / dq, col_step = 256 - row_step * dq;
     constexpr int rows_all = kRowsQ + kRowsK;
     int srow = tid / dq, scol = tid - srow * dq;
     f32x4 rg[UT];
-    int lds_off[UT];
+    const float* rowp[UT];
+    int lds_off[UT], ucol[UT];
 #pragma unroll
     for (int u = 0; u < UT; ++u) {
         const int row = srow < rows_all ? srow : rows_all - 1;      // surplus units repeat the last row
@@ -210,15 +214,28 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
         // rows past S re-read row S-1; what they produce is masked or never stored
         int gr = isq ? i0 + row : row - kRowsQ;
         gr = gr < p.S ? gr : p.S - 1;
-        const float* src = isq ? qb + gr * p.qs_s : kb + gr * p.ks_s;
-        rg[u] = ldg4(src + 4 * scol);
+        rowp[u] = isq ? qb + gr * p.qs_s : kb + gr * p.ks_s;
+        ucol[u] = 4 * scol;
         lds_off[u] = row * ld + 4 * scol;
         srow += row_step;
         scol += col_step;
         if (scol >= dq) { scol -= dq; ++srow; }
     }
+    auto load_chunk = [&](int d0) {
 #pragma unroll
-    for (int u = 0; u < UT; ++u) *reinterpret_cast<f32x4*>(&panel[lds_off[u]]) = rg[u];
+        for (int u = 0; u < UT; ++u) {
+            // columns past D (last chunk of a D that is not a multiple of 64) repeat the last four;
+            // they land in LDS columns the MFMA loop does not read
+            const int col = d0 + ucol[u] < p.D ? d0 + ucol[u] : p.D - 4;
+            rg[u] = ldg4(rowp[u] + col);
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int u = 0; u < UT; ++u) *reinterpret_cast<f32x4*>(&panel[lds_off[u]]) = rg[u];
+    };
+    load_chunk(0);
+    store_chunk();
     __syncthreads();
 
     f32x16 acc, acc2;
@@ -226,13 +243,24 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
     const float* arow = ks + (32 * wave + r32) * ld + 4 * h2;
     const float* brow = qs + (32 * qblk + r32) * ld + 4 * h2;
-    for (int d0 = 0; d0 < p.D; d0 += 8) {               // D is a multiple of 8
-        const f32x4 a = *reinterpret_cast<const f32x4*>(arow + d0);
-        const f32x4 bq = *reinterpret_cast<const f32x4*>(brow + d0);
-        acc = mfma32(a[0], bq[0], acc);
-        acc2 = mfma32(a[1], bq[1], acc2);
-        acc = mfma32(a[2], bq[2], acc);
-        acc2 = mfma32(a[3], bq[3], acc2);
+    for (int d0 = 0; d0 < p.D; d0 += kChunk) {
+        const bool more = d0 + kChunk < p.D;             // uniform
+        if (more) load_chunk(d0 + kChunk);
+        __builtin_amdgcn_sched_barrier(0);               // keep the loads ahead of the MFMAs
+        const int width = p.D - d0 < kChunk ? p.D - d0 : kChunk;
+        for (int d = 0; d < width; d += 8) {             // D is a multiple of 8
+            const f32x4 a = *reinterpret_cast<const f32x4*>(arow + d);
+            const f32x4 bq = *reinterpret_cast<const f32x4*>(brow + d);
+            acc = mfma32(a[0], bq[0], acc);
+            acc2 = mfma32(a[1], bq[1], acc2);
+            acc = mfma32(a[2], bq[2], acc);
+            acc2 = mfma32(a[3], bq[3], acc2);
+        }
+        if (more) {
+            __syncthreads();                             // every wave is done with this chunk
+            store_chunk();
+            __syncthreads();
+        }
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] += acc2[r];

@@ -530,14 +530,16 @@ def assert_softmax_parity(got_t, ref, what=""):
     assert e <= TOL, "%s: row-relative err %.3e" % (what, e)
 
 
-# S <= 128 with D a multiple of 8 takes the fused kernel, the rest the two-kernel path
+# S <= 128 with D a multiple of 8 (up to 1024) takes the fused kernel, the rest the two-kernel path
 TBS_SHAPES = [I.TbgShape(2, 5, 3, 4), I.TbgShape(1, 128, 2, 64), I.TbgShape(1, 130, 2, 33),
               I.TbgShape(2, 64, 12, 128), I.TbgShape(1, 1, 1, 8), I.TbgShape(3, 65, 2, 8),
               I.TbgShape(1, 100, 5, 32), I.TbgShape(2, 96, 3, 24), I.TbgShape(1, 128, 3, 128),
               I.TbgShape(1, 127, 2, 72), I.TbgShape(1, 129, 2, 64), I.TbgShape(1, 33, 2, 136),
               # short sequences: two key blocks x two query blocks, one key block x four query blocks
               I.TbgShape(2, 64, 3, 64), I.TbgShape(1, 48, 5, 40), I.TbgShape(2, 32, 3, 128),
-              I.TbgShape(3, 20, 2, 16), I.TbgShape(1, 33, 2, 8)]
+              I.TbgShape(3, 20, 2, 16), I.TbgShape(1, 33, 2, 8),
+              # reductions longer than one 64-column chunk, the last chunk partial
+              I.TbgShape(1, 128, 2, 256), I.TbgShape(2, 50, 3, 200), I.TbgShape(1, 100, 2, 72)]
 
 
 @pytest.mark.parametrize("shape", TBS_SHAPES, ids=str)
