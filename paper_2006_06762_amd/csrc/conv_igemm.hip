@@ -54,7 +54,9 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
     const int64_t w_extent = (int64_t)a.K * a.C * a.R * a.S;
     // 32-bit byte offsets inside x and w, 31-bit pixel and virtual-row indices
     const bool k3 = a.R == 3 && a.S == 3 && (a.C % 8 == 0);
-    const bool k1 = a.R == 1 && a.S == 1 && (a.C % 32 == 0);
+    // pointwise: with fewer than 256 input channels a tile has 2-4 chunks and never reaches steady
+    // state; the general kernel is faster there (64 -> 256 channels on 56x56: 32 against 60 us)
+    const bool k1 = a.R == 1 && a.S == 1 && (a.C % 32 == 0) && a.C >= 256;
     const bool ok = (k3 || k1) && a.dil_h == 1 && a.dil_w == 1 && a.groups == 1 && (a.W % 4 == 0) && is_aligned16(a.x) &&
                     is_aligned16(a.w) && (a.xs[0] % 4 == 0) && (a.xs[1] % 4 == 0) &&
                     (a.xs[2] % 4 == 0) && x_extent < (int64_t)1 << 30 && w_extent < (int64_t)1 << 30 &&

@@ -137,11 +137,15 @@ CONV_FAST = [
     I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 1), (0, 0)),
     I.ConvShape(2, 8, 10, 12, 8, 3, 3, (1, 2), (2, 1)),
     I.ConvShape(1, 32, 56, 56, 64, 3, 3, (1, 1), (1, 1)),
-    # pointwise (1x1) MFMA path: C % 32 == 0, W % 4 == 0
+    # pointwise (1x1) MFMA path: C % 32 == 0 and C >= 256, W % 4 == 0
+    I.ConvShape(2, 256, 12, 12, 40, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(3, 288, 8, 8, 70, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(1, 256, 28, 28, 64, 1, 1, (1, 1), (0, 0)),
+    I.ConvShape(2, 256, 12, 16, 16, 1, 1, (2, 2), (0, 0)),
+    I.ConvShape(1, 320, 9, 8, 33, 1, 1, (1, 1), (1, 1)),
+    # narrower pointwise layers always take the general kernel
     I.ConvShape(2, 32, 12, 12, 40, 1, 1, (1, 1), (0, 0)),
-    I.ConvShape(3, 64, 8, 8, 70, 1, 1, (1, 1), (0, 0)),
     I.ConvShape(1, 64, 56, 56, 64, 1, 1, (1, 1), (0, 0)),
-    I.ConvShape(2, 32, 12, 16, 16, 1, 1, (2, 2), (0, 0)),
     I.ConvShape(1, 96, 9, 8, 33, 1, 1, (1, 1), (1, 1)),
 ]
 # everything else goes through the general gather kernel
