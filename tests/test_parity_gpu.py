@@ -426,6 +426,11 @@ DW_SHAPES = [
     I.ConvShape(1, 4, 5, 5, 4, 5, 5, (1, 1), (4, 4)),
     I.ConvShape(1, 1, 64, 64, 1, 1, 1, (1, 1), (0, 0)),
     I.ConvShape(1, 3, 20, 65, 3, 2, 4, (3, 2), (1, 2)),
+    # stride-2 register-sliding kernel (width a multiple of 8): odd height, a ragged row chunk,
+    # planes that do not fill the last wave
+    I.ConvShape(2, 5, 16, 24, 5, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(1, 3, 9, 8, 3, 3, 3, (2, 2), (1, 1)),
+    I.ConvShape(3, 7, 30, 56, 7, 3, 3, (2, 2), (1, 1)),
 ]
 
 
