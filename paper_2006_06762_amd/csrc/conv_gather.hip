@@ -172,7 +172,7 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);
     else err = launch_tile<64, 64>(a, g, stream);
     if (err != hipSuccess || g.ksplit == 1) return err;
-    const int64_t threads = (int64_t)a.K * (g.Mpad / 4);
+    const int64_t threads = (int64_t)a.K * (g.Mpad / 4) * kReduceLanes;
     return launch_kernel(conv_splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                          a, g);
 }

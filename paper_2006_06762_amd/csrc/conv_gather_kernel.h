@@ -294,36 +294,47 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
         }
 }
 
-// Sums the ksplit partial tiles in split order and runs the epilogue: one thread per
-// (output channel, four consecutive pixels).
+// Sums the ksplit partial tiles and runs the epilogue.  Eight lanes share one (output channel,
+// four consecutive pixels): lane j adds the partials of splits j, j + 8, ... (all its loads in
+// flight at once), then the eight sums are combined by a fixed shuffle tree, so the result does
+// not depend on scheduling.  One memory round trip however many splits there are.
+constexpr int kReduceLanes = 8;
+
 __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs p, const Plan g)
 {
     const int mquads = g.Mpad >> 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int co = (int)(idx / mquads), mq = 4 * (int)(idx - (int64_t)co * mquads);
-    if (co >= p.K || mq >= g.Mtot) return;
-    // eight partial tiles in flight at a time; the sum runs in split order whatever the batching
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = gid / kReduceLanes;
+    const int sub = (int)(gid - idx * kReduceLanes);
+    int co = (int)(idx / mquads);
+    const int mq = 4 * (int)(idx - (int64_t)co * mquads);
+    const bool live = co < p.K && mq < g.Mtot;
+    co = co < p.K ? co : p.K - 1;                 // surplus lanes redo the last channel, store nothing
     // channel co sits in column (its group's first tile) * bn + (index inside the group)
     const int grp = g.d_kg.div(co);
     const float* src = p.ws + ((int64_t)grp * g.tiles_ng * g.bn + (co - grp * g.Kg)) * g.Mpad + mq;
     const int64_t step = (int64_t)g.Kpad * g.Mpad;
     f32x4 v = zero4();
-    int s = 0;
-    for (; s + 8 <= g.ksplit; s += 8) {
-        f32x4 t[8];
+    int s = sub;
+    for (; s + 3 * kReduceLanes < g.ksplit; s += 4 * kReduceLanes) {
+        f32x4 t[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) t[i] = ldg4(src + (s + i) * step);
+        for (int i = 0; i < 4; ++i) t[i] = ldg4(src + (s + i * kReduceLanes) * step);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] += t[i][r];
     }
-    for (; s < g.ksplit; ++s) {
+    for (; s < g.ksplit; s += kReduceLanes) {
         const f32x4 t = ldg4(src + s * step);
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] += t[r];
     }
-    store_quad(p, g, mq, co, v);
+#pragma unroll
+    for (int o = 1; o < kReduceLanes; o <<= 1)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] += __shfl_xor(v[r], o);
+    if (live && sub == 0) store_quad(p, g, mq, co, v);
 }
 
 }  // namespace gconv
