@@ -301,6 +301,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    from paper_2006_06762_amd import build as hip_build
+    hip_build.ensure_built()
     from paper_2006_06762_amd import binding as anr
     from paper_2006_06762_amd import inputs as I
 

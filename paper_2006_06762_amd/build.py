@@ -50,5 +50,11 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def ensure_built(verbose: bool = False) -> str:
+    """Build the library only if no built one is there (tests, the smoke run and the benchmark
+    load what is built; after a change to a source, build again explicitly)."""
+    return LIB if os.path.exists(LIB) else build(verbose=verbose)
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra=sys.argv[1:]))

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the built library; a tree that has none yet gets it built once (hipcc
+    # cross-compiles without a GPU)
+    from paper_2006_06762_amd import build as hip_build
+    hip_build.ensure_built()
 
 
 @pytest.fixture(scope="session")
