@@ -597,6 +597,110 @@ def test_tbs_config_shape(anr):
     assert_softmax_parity(out, oracle.tbs(cfg["q"], cfg["k"]), what="TBS config")
 
 
+# ------------------------------------------------------------------ seeded random geometries
+def _random_conv_shapes(count, seed):
+    g = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    while len(shapes) < count:
+        groups = int(g.choice([1, 1, 1, 2, 3, 4]))
+        C = groups * int(g.integers(1, 13))
+        K = groups * int(g.integers(1, 41))
+        R, S = int(g.integers(1, 6)), int(g.integers(1, 6))
+        dil = (int(g.integers(1, 4)), int(g.integers(1, 4)))
+        stride = (int(g.integers(1, 4)), int(g.integers(1, 4)))
+        pad = (int(g.integers(0, 4)), int(g.integers(0, 4)))
+        H, W = int(g.integers(1, 24)), int(g.integers(1, 24))
+        s = I.ConvShape(int(g.integers(1, 4)), C, H, W, K, R, S, stride, pad, dil, groups)
+        if s.OH >= 1 and s.OW >= 1:
+            shapes.append(s)
+    return shapes
+
+
+def test_conv2d_random_geometries(anr):
+    """Forty seeded random geometries (kernel, stride, padding, dilation, groups, odd sizes) with
+    small-integer values: the general kernel must agree with the oracle bit for bit."""
+    for i, s in enumerate(_random_conv_shapes(40, 900)):
+        x, w = I.conv_inputs(s, 901 + i, ints=True)
+        buf, y = guarded((s.N, s.K, s.OH, s.OW))
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil, groups=s.groups)
+        check_guard(buf)
+        ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups)
+        assert_parity(y, ref, exact=True, what="random conv %d %s" % (i, s))
+
+
+def test_conv2d_random_geometries_tuned_kernel(anr, monkeypatch):
+    """Seeded random geometries inside what the tuned patch-staging kernel takes (3x3 with C % 8 == 0,
+    1x1 with C % 32 == 0 and C >= 256, W % 4 == 0), forced onto it whatever the tile count."""
+    monkeypatch.setenv("ANR_CONV_MIN_TUNED_WGS", "0")
+    g = np.random.Generator(np.random.PCG64(980))
+    for i in range(40):
+        if g.random() < 0.75:
+            R, C = 3, 8 * int(g.integers(1, 6))
+        else:
+            R, C = 1, 32 * int(g.integers(8, 11))
+        st = int(g.integers(1, 3))
+        pad = (int(g.integers(0, 3)), int(g.integers(0, 3)))
+        H, W = int(g.integers(3, 40)), 4 * int(g.integers(1, 16))
+        s = I.ConvShape(int(g.integers(1, 5)), C, H, W, int(g.integers(1, 100)), R, R, (st, st), pad)
+        if s.OH < 1 or s.OW < 1:
+            continue
+        x, w = I.conv_inputs(s, 981 + i, ints=True)
+        buf, y = guarded((s.N, s.K, s.OH, s.OW))
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+        check_guard(buf)
+        assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), exact=True, what="random tuned conv %d %s" % (i, s))
+
+
+def test_dwconv_random_geometries(anr):
+    g = np.random.Generator(np.random.PCG64(950))
+    for i in range(30):
+        C = int(g.integers(1, 20))
+        R, S = int(g.integers(1, 5)), int(g.integers(1, 5))
+        stride = (int(g.integers(1, 3)), int(g.integers(1, 3)))
+        pad = (int(g.integers(0, 3)), int(g.integers(0, 3)))
+        dil = (int(g.integers(1, 3)), int(g.integers(1, 3)))
+        H, W = int(g.integers(1, 40)), int(g.choice([4, 7, 8, 12, 14, 16, 24, 28, 33, 56]))
+        s = I.ConvShape(int(g.integers(1, 4)), C, H, W, C, R, S, stride, pad, dil)
+        if s.OH < 1 or s.OW < 1:
+            continue
+        x, w = I.dwconv_inputs(s, 951 + i, ints=True)
+        buf, y = guarded((s.N, s.C, s.OH, s.OW))
+        anr.dwconv(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil)
+        check_guard(buf)
+        ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.C)
+        assert_parity(y, ref, exact=True, what="random dwconv %d %s" % (i, s))
+
+
+def test_gemm_random_shapes(anr):
+    g = np.random.Generator(np.random.PCG64(960))
+    for i in range(30):
+        M, N, K = int(g.integers(1, 200)), int(g.integers(1, 200)), int(g.integers(1, 200))
+        if g.random() < 0.5:            # the aligned kernels
+            N, K = 4 * ((N + 3) // 4), 4 * ((K + 3) // 4)
+        batch = int(g.choice([1, 1, 2, 5]))
+        A, B = I.gemm_inputs(I.GemmShape(M, N, K, batch), 961 + i, ints=True)
+        shape = (batch, M, N) if batch > 1 else (M, N)
+        buf, C = guarded(shape)
+        anr.gemm(dev(A), dev(B), C)
+        check_guard(buf)
+        assert_parity(C, oracle.gemm(A, B), exact=True, what="random gemm %d %s" % (i, (M, N, K, batch)))
+
+
+def test_tbs_random_shapes(anr):
+    g = np.random.Generator(np.random.PCG64(970))
+    for i in range(20):
+        s = I.TbgShape(int(g.integers(1, 3)), int(g.integers(1, 140)), int(g.integers(1, 4)),
+                       int(g.choice([4, 8, 12, 16, 24, 40, 64, 72, 128])))
+        q, k = I.tbg_inputs(s, 971 + i)
+        q = (q * 0.35).astype(np.float32)
+        buf, out = guarded((s.B, s.H, s.S, s.S))
+        anr.tbs(dev(q), dev(k), out)
+        check_guard(buf)
+        assert_softmax_parity(out, oracle.tbs(q, k), what="random tbs %d %s" % (i, s))
+        anr.tbg(dev(q), dev(k), out)
+        assert_parity(out, oracle.tbg(q, k), what="random tbg %d %s" % (i, s))
+
+
 # ------------------------------------------------------------------ NRM
 NRM_TOL = 2e-6      # relative: fp32 partial sums of at most a few thousand squares each, then a tree
 
