@@ -16,8 +16,7 @@
 // prefetches tile t+1 while multiplying tile t (11.9 us against 8.8 us: a single tile of
 // look-ahead does not cover the ~2 us loaded memory latency), and one work-group per CU
 // that requests the panels of its three tiles at once and shares panels between them
-// (10.8 us: a CU ingests only ~10 bytes per clock from cold HBM, and a wave that is stuck
-// issuing loads cannot multiply).  Three independent work-groups per CU keep more requests
+// (10.8 us: a wave that is stuck issuing a long run of loads cannot multiply).  Three independent work-groups per CU keep more requests
 // in flight and win.  Writing the tile through LDS so that every store instruction covers four
 // whole 256-byte rows instead of two 128-byte pieces was also slower (8.7 against 8.4 us).
 #pragma once
