@@ -18,7 +18,7 @@ constexpr int kCUs = 256;
 constexpr double kLaunchUs = 2.0;            // launch plus prologue and epilogue
 constexpr double kWsBytesPerUs = 3.0e6;      // workspace traffic, bytes per microsecond
 
-bool make_plan(const ConvArgs& a, Plan* g)
+bool make_plan(const ConvArgs& a, Plan* g, bool allow_taps = true)
 {
     const int64_t x_extent = (int64_t)(a.N - 1) * a.xs[0] + (int64_t)(a.C - 1) * a.xs[1] +
                              (int64_t)(a.H - 1) * a.xs[2] + a.W;
@@ -39,7 +39,14 @@ bool make_plan(const ConvArgs& a, Plan* g)
     g->Kg = a.K / a.groups;
     g->Ktot = g->Cg * g->RS;
     g->d_kg = make_fastdiv(g->Kg);
-    g->nchunks = (g->Ktot + KC - 1) / KC;
+    // 3 x 3 and 1 x 1 kernels whose channels fill whole chunks take the form with compile-time taps
+    g->taps = 0;
+    g->kc = KC;
+    if (allow_taps && is_aligned16(a.w)) {
+        if (a.R == 3 && a.S == 3 && g->Cg % 4 == 0) { g->taps = 9; g->kc = 36; }
+        if (a.R == 1 && a.S == 1 && g->Cg % 32 == 0) { g->taps = 1; g->kc = 32; }
+    }
+    g->nchunks = (g->Ktot + g->kc - 1) / g->kc;
     g->w_vec = (g->Ktot % 4 == 0) && is_aligned16(a.w);
     g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) &&
                    is_aligned16(a.y);
@@ -96,11 +103,51 @@ double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
     return us;
 }
 
+// The same estimate for conv_taps_kernel, which runs 64 x 64 tiles only (the larger tiles were
+// slower on every layer shape of a sweep over ResNet-style 3 x 3 and 1 x 1 layers at batch 1, 4
+// and 16).  A work-group's chain is a prologue plus its chunks; a chunk takes kLoneUs when the
+// work-group has the CU to itself and kChunkUs per resident work-group once they saturate it.
+double estimate_taps_us(const Plan& g, const ConvArgs& a, int ks)
+{
+    constexpr double kPrologueUs = 0.9, kLoneUs = 0.78, kChunkUs = 0.65;   // per chunk of 36
+    constexpr double kMainUs = 2.6, kReduceUs = 4.5, kWsRate = 4.85e6;     // launches; workspace bytes per us
+    const int64_t tiles = (int64_t)((g.Mtot + 63) / 64) * a.groups * ((g.Kg + 63) / 64);
+    const int cps = (g.nchunks + ks - 1) / ks;
+    const int ks_eff = (g.nchunks + cps - 1) / cps;
+    const int64_t wgs = tiles * ks_eff;
+    const double per_cu = (double)((wgs + kCUs - 1) / kCUs);
+    const double resident = per_cu < 4.0 ? per_cu : 4.0;
+    const double per_chunk = resident * kChunkUs > kLoneUs ? resident * kChunkUs : kLoneUs;
+    double us = kMainUs + (per_cu / resident) * (kPrologueUs + cps * (g.kc / 36.0) * per_chunk);
+    if (ks_eff > 1) us += kReduceUs + 2.0 * 4.0 * ks_eff * tiles * 4096.0 / kWsRate;
+    return us;
+}
+
 bool choose_tile(const ConvArgs& a, Plan* g)
 {
     double best = 0.0;
     bool have = false;
     int bm = 0, bn = 0, bks = 1;
+    if (g->taps) {
+        const int64_t tiles = (int64_t)((g->Mtot + 63) / 64) * a.groups * ((g->Kg + 63) / 64);
+        if (tiles >= ((int64_t)1 << 24)) return false;
+        const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;
+        int last_cps = 0;
+        for (int ks = 1; ks <= most; ++ks) {
+            const int cps = (g->nchunks + ks - 1) / ks;
+            if (cps == last_cps) continue;
+            last_cps = cps;
+            if (4.0 * ks * tiles * 4096.0 > 256e6) break;
+            const double us = estimate_taps_us(*g, a, ks);
+            if (!have || us < best) {
+                have = true;
+                best = us;
+                bks = ks;
+            }
+        }
+        set_tile(a, g, 64, 64, bks);
+        return true;
+    }
     for (const Tile& t : kTiles) {
         const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * a.groups * ((g->Kg + t.bn - 1) / t.bn);
         if (tiles >= ((int64_t)1 << 24)) continue;
@@ -131,11 +178,11 @@ size_t plan_workspace(const Plan& g)
     return g.ksplit > 1 ? sizeof(float) * (size_t)g.ksplit * g.Kpad * g.Mpad : 0;
 }
 
-template <int BM, int BN>
-hipError_t launch_tile(const ConvArgs& a, const Plan& g, hipStream_t stream)
+template <int BM, int BN, bool MASK>
+hipError_t launch_tile_as(const ConvArgs& a, const Plan& g, hipStream_t stream)
 {
     const size_t lds_bytes = sizeof(float) * 2 * (size_t)(BM + BN) * WS;
-    auto kern = conv_gather_kernel<BM, BN>;
+    auto kern = conv_gather_kernel<BM, BN, MASK>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -145,14 +192,41 @@ hipError_t launch_tile(const ConvArgs& a, const Plan& g, hipStream_t stream)
     return launch_kernel(kern, dim3(grid), dim3(256), lds_bytes, stream, a, g);
 }
 
+template <int BM, int BN, int R_, int S_>
+hipError_t launch_tile_taps(const ConvArgs& a, const Plan& g, hipStream_t stream)
+{
+    const size_t lds_bytes = sizeof(float) * 2 * (size_t)(BM + BN) * (g.kc + 2);
+    auto kern = conv_taps_kernel<BM, BN, R_, S_>;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
+    return launch_kernel(kern, dim3(grid), dim3(256), lds_bytes, stream, a, g);
+}
+
+template <int BM, int BN>
+hipError_t launch_tile(const ConvArgs& a, const Plan& g, hipStream_t stream)
+{
+    // up to 31 taps fit the per-pixel mask of the cheaper gather
+    return g.RS <= 31 ? launch_tile_as<BM, BN, true>(a, g, stream) : launch_tile_as<BM, BN, false>(a, g, stream);
+}
+
 }  // namespace
 
 hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stream);
 
+// What the call may need: the larger of the two kernel forms' needs, so that the figure for a
+// shape does not depend on whether the weight pointer turns out to be 16-byte aligned.
 size_t conv2d_gather_workspace_bytes(const ConvArgs& a)
 {
-    Plan g;
-    return make_plan(a, &g) && choose_tile(a, &g) ? plan_workspace(g) : 0;
+    size_t need = 0;
+    for (const bool allow_taps : {true, false}) {
+        Plan g;
+        if (make_plan(a, &g, allow_taps) && choose_tile(a, &g) && plan_workspace(g) > need) need = plan_workspace(g);
+    }
+    return need;
 }
 
 hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken)
@@ -168,7 +242,10 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     const size_t need = plan_workspace(g);
     if (need > 0 && (a.ws == nullptr || a.ws_bytes < need || !is_aligned16(a.ws))) return hipErrorInvalidValue;
     hipError_t err;
-    if (g.bm == 128 && g.bn == 128) err = launch_tile<128, 128>(a, g, stream);
+    if (g.taps) {
+        if (g.bm != 64 || g.bn != 64) return hipErrorInvalidValue;
+        err = g.taps == 9 ? launch_tile_taps<64, 64, 3, 3>(a, g, stream) : launch_tile_taps<64, 64, 1, 1>(a, g, stream);
+    } else if (g.bm == 128 && g.bn == 128) err = launch_tile<128, 128>(a, g, stream);
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);
     else err = launch_tile<64, 64>(a, g, stream);
     if (err != hipSuccess || g.ksplit == 1) return err;

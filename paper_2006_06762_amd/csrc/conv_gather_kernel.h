@@ -52,6 +52,8 @@ struct Plan {
     uint32_t x_bytes, w_bytes;
     FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles, d_tiles_ng, d_kg;
     int bm, bn;                  // chosen tile (host side)
+    int kc;                      // reduction elements per chunk: KC, or 36 for the 3 x 3 form of conv_taps_kernel
+    int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1
 };
 
 // Epilogue of one accumulator quad: registers 4q .. 4q+3 of a lane are pixels mq .. mq+3 of
@@ -82,7 +84,41 @@ __device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int
     }
 }
 
-template <int BM, int BN>
+// Epilogue of a work-group's tile.  Accumulator register r of lane (h, r32) is pixel
+// 8*(r/4) + 4*h + r%4 and channel r32 of its 32 x 32 block; waves are 2 x 2 with MB x NB blocks
+// each.  With a split reduction the partial tile goes to the workspace, which is padded to
+// whole tiles: no bounds to test.
+template <int MB, int NB>
+__device__ __forceinline__ void store_tile(const ConvArgs& p, const Plan& g, const f32x16 (&acc)[MB][NB], int split,
+                                           int tile_n, int m0, int cl0, int cog, int wm, int wn, int r32, int h)
+{
+    constexpr int BN = 64 * NB;
+    float* const wsp = p.ws + ((int64_t)split * g.Kpad + tile_n * BN + wn * NB * 32 + r32) * g.Mpad + m0 +
+                       wm * MB * 32 + 4 * h;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int tcol = (wn * NB + nb) * 32 + r32;             // column inside the tile
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 v = {acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
+                                 acc[mb][nb][4 * q + 3]};
+                if (g.ksplit > 1) {
+                    stg4(wsp + (int64_t)(nb * 32) * g.Mpad + mb * 32 + 8 * q, v);
+                } else if (cl0 + tcol < g.Kg) {
+                    store_quad(p, g, m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h, cog + cl0 + tcol, v);
+                }
+            }
+        }
+}
+
+// MASK: the kernel has at most 31 taps, so which taps of a pixel fall outside the image fits one
+// register per lane and a gather load costs three vector-ALU instructions (bit test, add,
+// and-or) instead of the two displacement adds, two compares and a select of the general form.
+// Between MFMAs every vector-ALU instruction of any wave on the SIMD costs matrix time, and with
+// 64 x 64 tiles the general form spends more of it on the gather than on the MFMAs.
+template <int BM, int BN, bool MASK>
 __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, const Plan g)
 {
     constexpr int MB = BM / 64, NB = BN / 64;       // 32x32 blocks per wave (waves are 2 x 2)
@@ -129,6 +165,18 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
         // may be negative; valid taps make it >= 0.  The group's first input channel is folded in.
         xbase = (int)(n * p.xs[0] + (int64_t)grp * g.Cg * p.xs[1] + ihb * p.xs[2] + iwb);
     }
+    // bit t set: tap t of this pixel lies outside the image; bit 31 (no kernel has a tap 31
+    // here) stands for the reduction indices past the end
+    uint32_t notmask = 0x80000000u;
+    if (MASK) {
+        for (int r = 0; r < p.R; ++r)
+            for (int s = 0; s < p.S; ++s) {
+                const bool ok = ((unsigned)(ihb + r * p.dil_h) < (unsigned)p.H) &
+                                ((unsigned)(iwb + s * p.dil_w) < (unsigned)p.W);
+                notmask |= ok ? 0u : 1u << (r * p.S + s);
+            }
+    }
+    const int xbase4 = 4 * xbase;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t wrsrc =
@@ -140,21 +188,39 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
     float ra[2][AU];
     float rb[2][BU1];                     // BU4 16-byte units or BU1 single floats: the same registers
 
+    // byte offsets of this lane's 16-byte weight units inside a chunk (columns past the group
+    // repeat its last one, never stored)
+    uint32_t wvoff[BU4];
+#pragma unroll
+    for (int j = 0; j < BU4; ++j) {
+        int co = cl0 + (tid >> 3) + 32 * j;
+        co = cog + (co < g.Kg ? co : g.Kg - 1);
+        wvoff[j] = 4u * (uint32_t)(co * g.Ktot + 4 * (tid & 7));
+    }
+
     // The tap table of one chunk: for each of its KC reduction indices the offset of the tap
     // (c, r, s) inside an image and its row and column displacement.  32 threads fill it a chunk
     // ahead, so a gather load costs one broadcast LDS read instead of two scalar divisions.
+    // The waves take turns at it: the divisions are vector-ALU work of one SIMD.
     auto fill_taps = [&](int chunk, int slot) {
-        if (tid < KC) {
-            const int k = chunk * KC + tid;
+        if (wave == (chunk & 3) && lane < KC) {
+            const int k = chunk * KC + lane;
             const int c = g.d_rs.div(k), tap = k - c * g.RS;
             const int r = g.d_s.div(tap), s = tap - r * p.S;
-            // offset of the tap, then row and column displacement packed as two 16-bit fields; a k
-            // past the end gets a row displacement no pixel can be in bounds with
-            const int dr = k < g.Ktot ? r * p.dil_h : kNoRow;
+            const int koff = (int)(c * p.xs[1] + (r * p.dil_h) * p.xs[2] + s * p.dil_w);
             i32x2 e;
-            e[0] = (int)(c * p.xs[1] + (r * p.dil_h) * p.xs[2] + s * p.dil_w);
-            e[1] = (dr << 16) | (s * p.dil_w);
-            ktab[slot * KC + tid] = e;
+            if (MASK) {
+                // byte offset of the tap and its number
+                e[0] = 4 * koff;
+                e[1] = k < g.Ktot ? tap : 31;
+            } else {
+                // offset of the tap, then row and column displacement packed as two 16-bit fields; a
+                // k past the end gets a row displacement no pixel can be in bounds with
+                const int dr = k < g.Ktot ? r * p.dil_h : kNoRow;
+                e[0] = koff;
+                e[1] = (dr << 16) | (s * p.dil_w);
+            }
+            ktab[slot * KC + lane] = e;
         }
     };
     auto load_chunk = [&](int chunk, int slot, auto set_c) {
@@ -168,20 +234,27 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
             for (int j = 0; j < 8; ++j) e[j] = ktab[slot * KC + akg + KG * (j0 + j)];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int dr = e[j][1] >> 16, ds = e[j][1] & 0xffff;
-                const bool ok = ((unsigned)(ihb + dr) < (unsigned)p.H) & ((unsigned)(iwb + ds) < (unsigned)p.W);
-                const uint32_t off = ok ? 4u * (uint32_t)(xbase + e[j][0]) : kOutOfRange;
+                uint32_t off;
+                if (MASK) {
+                    // -1 if the tap is outside the image: the offset then gets its top bit set
+                    const int out = __builtin_amdgcn_sbfe((int)notmask, (unsigned)e[j][1], 1u);
+                    off = (uint32_t)(xbase4 + e[j][0]) | ((uint32_t)out & kOutOfRange);
+                } else {
+                    const int dr = e[j][1] >> 16, ds = e[j][1] & 0xffff;
+                    const bool ok = ((unsigned)(ihb + dr) < (unsigned)p.H) & ((unsigned)(iwb + ds) < (unsigned)p.W);
+                    off = ok ? 4u * (uint32_t)(xbase + e[j][0]) : kOutOfRange;
+                }
                 ra[set][j0 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
             }
         }
+        // weights: the lane's part of the offset is fixed (wvoff), the chunk's part is uniform and
+        // rides in the scalar offset; only the last chunk can reach past the end of a row
         if (g.w_vec) {
+            const bool past = k0 + 4 * (tid & 7) >= g.Ktot;
 #pragma unroll
             for (int j = 0; j < BU4; ++j) {
-                const int col = (tid >> 3) + 32 * j, k = k0 + 4 * (tid & 7);
-                int co = cl0 + col;
-                co = cog + (co < g.Kg ? co : g.Kg - 1);           // columns past the group repeat its last, never stored
-                const uint32_t off = k < g.Ktot ? 4u * (uint32_t)(co * g.Ktot + k) : kOutOfRange;
-                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0));
+                const uint32_t off = past ? kOutOfRange : wvoff[j];
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 4 * k0, 0));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) rb[set][4 * j + i] = v[i];
             }
@@ -273,25 +346,172 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
         if (c + 1 < c_end) iteration(c + 1, S1{});
     }
 
-    // ---- accumulator register r of lane (h, r32): pixel 8*(r/4) + 4*h + r%4, channel r32 of the block
+    store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
+}
+
+// The same convolution for 3 x 3 and 1 x 1 kernels whose channel count fills whole chunks: a
+// chunk is CPC whole input channels (4 x 9 or 32 x 1 reduction indices), so which tap a gather
+// load fetches is known at compile time.  A lane keeps one byte offset per tap (its pixel's
+// base plus the tap's displacement, or the out-of-range marker where the tap leaves the image)
+// and the channel rides in the scalar offset of the buffer load: the loop between two barriers
+// holds no vector-ALU instruction for addresses or bounds, no tap table and no tail handling.
+// On this hardware every vector-ALU instruction of any wave on a SIMD takes about eight cycles
+// from the matrix pipe, and counters show the general kernel above spending 35-40 % of its
+// SIMD time on them.  Weights: a chunk of a row is KC consecutive floats of the OIHW order.
+template <int BM, int BN, int R_, int S_>
+__global__ __launch_bounds__(256) void conv_taps_kernel(const ConvArgs p, const Plan g)
+{
+    constexpr int T = R_ * S_;
+    constexpr int CPC = T == 1 ? 32 : 4;            // channels per chunk
+    constexpr int KCT = CPC * T;                    // reduction elements per chunk
+    constexpr int WST = KCT + 2;                    // LDS row stride, floats
+    constexpr int MB = BM / 64, NB = BN / 64;
+    constexpr int KG = 256 / BM;                    // threads per pixel in the A gather
+    constexpr int CPT = CPC / KG;                   // channels of a chunk one thread gathers
+    constexpr int AU = CPT * T;                     // A elements per thread and chunk
+    constexpr int UPR = KCT / 4;                    // 16-byte units per weight row and chunk
+    constexpr int BUNITS = BN * UPR;
+    constexpr int BU = (BUNITS + 255) / 256;        // B units per thread and chunk
+    constexpr int A_SZ = BM * WST, B_SZ = BN * WST;
+    static_assert(KCT % 4 == 0 && CPC % KG == 0, "chunk geometry");
+
+    extern __shared__ __attribute__((aligned(16))) float glds[];   // A[2][BM][WST], then B[2][BN][WST]
+    float* const lds_a = glds;
+    float* const lds_b = glds + 2 * A_SZ;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int split = g.d_tiles.div((int)blockIdx.x);
+    const int trem = (int)blockIdx.x - split * tiles;
+    const int tile_n = g.d_tiles_m.div(trem), tile_m = trem - tile_n * g.tiles_m;
+    const int grp = g.d_tiles_ng.div(tile_n);
+    const int m0 = tile_m * BM, cl0 = (tile_n - grp * g.tiles_ng) * BN;
+    const int cog = grp * g.Kg;
+    const int c_begin = split * g.chunks_per_split;
+    const int c_end = c_begin + g.chunks_per_split < g.nchunks ? c_begin + g.chunks_per_split : g.nchunks;
+
+    // ---- the pixel this thread gathers for, and its byte offset for every tap
+    const int am = tid % BM;
+    const int akg = __builtin_amdgcn_readfirstlane(tid / BM);
+    uint32_t voff[T];
+    {
+        int m = m0 + am;
+        m = m < g.Mtot ? m : g.Mtot - 1;      // rows past the end repeat the last pixel, never stored
+        const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+        const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+        const int ihb = oh * p.stride_h - p.pad_h, iwb = ow * p.stride_w - p.pad_w;
+        const int xbase = (int)(n * p.xs[0] + (int64_t)grp * g.Cg * p.xs[1] + ihb * p.xs[2] + iwb);
+        const int xs2 = (int)p.xs[2];
+#pragma unroll
+        for (int r = 0; r < R_; ++r)
+#pragma unroll
+            for (int s = 0; s < S_; ++s) {
+                const bool ok = ((unsigned)(ihb + r * p.dil_h) < (unsigned)p.H) &
+                                ((unsigned)(iwb + s * p.dil_w) < (unsigned)p.W);
+                voff[r * S_ + s] = ok ? 4u * (uint32_t)(xbase + r * p.dil_h * xs2 + s * p.dil_w) : kOutOfRange;
+            }
+    }
+    // ---- this thread's weight units: unit u is 16 bytes of row u / UPR; slots past the tile's
+    //      units duplicate an earlier one (same data to the same place), columns past the group
+    //      repeat its last (never stored)
+    uint32_t wvoff[BU], wlds[BU];
+#pragma unroll
+    for (int j = 0; j < BU; ++j) {
+        const int u = (tid + 256 * j) % BUNITS;
+        const int row = u / UPR, q = u - row * UPR;
+        int co = cl0 + row;
+        co = cog + (co < g.Kg ? co : g.Kg - 1);
+        wvoff[j] = 4u * (uint32_t)(co * g.Ktot + 4 * q);
+        wlds[j] = (uint32_t)(row * WST + 4 * q);
+    }
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
+    const int xs1 = (int)p.xs[1];
+
+    // two chunks of look-ahead in registers, as in the general kernel
+    float ra[2][AU];
+    f32x4 rb[2][BU];
+    auto load_chunk = [&](int chunk, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        const int c0 = chunk * CPC + akg * CPT;                  // uniform over the wave
+#pragma unroll
+        for (int cc = 0; cc < CPT; ++cc)
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+                ra[set][cc * T + t] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)voff[t], 4 * (c0 + cc) * xs1, 0));
+#pragma unroll
+        for (int j = 0; j < BU; ++j)
+            rb[set][j] = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)wvoff[j], 4 * chunk * KCT, 0));
+    };
+    auto store_chunk = [&](int buf, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        float* const a = lds_a + buf * A_SZ + am * WST + akg * AU;
+        float* const b = lds_b + buf * B_SZ;
+#pragma unroll
+        for (int i = 0; i < AU; ++i) a[i] = ra[set][i];
+#pragma unroll
+        for (int j = 0; j < BU; ++j) {
+            f32x2* dst = reinterpret_cast<f32x2*>(b + wlds[j]);
+            const f32x2 lo = {rb[set][j][0], rb[set][j][1]}, hi = {rb[set][j][2], rb[set][j][3]};
+            dst[0] = lo;
+            dst[1] = hi;
+        }
+    };
+
+    f32x16 acc[MB][NB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int tcol = (wn * NB + nb) * 32 + r32;             // column inside the tile
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int mq = m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h;
-                const f32x4 v = {acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
-                                 acc[mb][nb][4 * q + 3]};
-                if (g.ksplit > 1) {
-                    // the workspace is padded to whole tiles: no bounds to test
-                    stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * BN + tcol) * g.Mpad + mq, v);
-                } else if (cl0 + tcol < g.Kg) {
-                    store_quad(p, g, mq, cog + cl0 + tcol, v);
-                }
-            }
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+
+    load_chunk(c_begin, S0{});
+    load_chunk(clampc(c_begin + 1), S1{});
+    store_chunk(0, S0{});
+    __syncthreads();
+
+    // Iteration c: LDS buffer P holds chunk c, register set P^1 chunk c+1, set P is free.
+    auto iteration = [&](int c, auto par_c) {
+        constexpr int P = decltype(par_c)::value;
+        load_chunk(clampc(c + 2), std::integral_constant<int, P>{});
+        __builtin_amdgcn_sched_barrier(0);
+        const float* a = lds_a + P * A_SZ + (wm * MB * 32 + r32) * WST + 2 * h;
+        const float* b = lds_b + P * B_SZ + (wn * NB * 32 + r32) * WST + 2 * h;
+#pragma unroll
+        for (int j = 0; j < KCT / 4; ++j) {
+            f32x2 av[MB], bv[NB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WST + 4 * j);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WST + 4 * j);
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
         }
+        store_chunk(P ^ 1, std::integral_constant<int, P ^ 1>{});
+        __syncthreads();
+    };
+    for (int c = c_begin; c < c_end; c += 2) {
+        iteration(c, S0{});
+        if (c + 1 < c_end) iteration(c + 1, S1{});
+    }
+    store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
 
 // Sums the ksplit partial tiles and runs the epilogue.  Eight lanes share one (output channel,

@@ -14,10 +14,6 @@ using V224x64 = Variant<7, 1, 1, 2, 2, 3, 3, 4>;   // 4 waves: two 7x1-block til
 using V224x32 = Variant<7, 1, 1, 1, 4, 3, 3, 4>;   // 4 waves share one 7x1-block tile along k
 using V128x64 = Variant<2, 2, 2, 1, 2, 3, 3, 4>;   // 4 waves, 2x2 blocks each, 2-way k split
 using V64x64 = Variant<2, 2, 1, 1, 4, 3, 3, 4>;    // 4 waves share one 2x2-block tile along k
-// 1x1 kernels (pointwise convolution): chunks of 32 channels
-using P224x64 = Variant<7, 1, 1, 2, 2, 1, 1, 16>;
-using P224x32 = Variant<7, 1, 1, 1, 4, 1, 1, 16>;
-using P64x64 = Variant<2, 2, 1, 1, 4, 1, 1, 16>;
 
 template <class V>
 void consider(const ConvArgs& a, double* best_cost, int* best, int id, Geom* g, size_t* lds)
@@ -53,11 +49,10 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
                              (int64_t)(a.H - 1) * a.xs[2] + a.W;
     const int64_t w_extent = (int64_t)a.K * a.C * a.R * a.S;
     // 32-bit byte offsets inside x and w, 31-bit pixel and virtual-row indices
+    // 3 x 3 only: pointwise layers were measured through this kernel as well (chunks of 32
+    // channels) and ran level with or behind conv_taps_kernel on every ResNet-style shape
     const bool k3 = a.R == 3 && a.S == 3 && (a.C % 8 == 0);
-    // pointwise: with fewer than 256 input channels a tile has 2-4 chunks and never reaches steady
-    // state; the general kernel is faster there (64 -> 256 channels on 56x56: 32 against 60 us)
-    const bool k1 = a.R == 1 && a.S == 1 && (a.C % 32 == 0) && a.C >= 256;
-    const bool ok = (k3 || k1) && a.dil_h == 1 && a.dil_w == 1 && a.groups == 1 && (a.W % 4 == 0) && is_aligned16(a.x) &&
+    const bool ok = k3 && a.dil_h == 1 && a.dil_w == 1 && a.groups == 1 && (a.W % 4 == 0) && is_aligned16(a.x) &&
                     is_aligned16(a.w) && (a.xs[0] % 4 == 0) && (a.xs[1] % 4 == 0) &&
                     (a.xs[2] % 4 == 0) && x_extent < (int64_t)1 << 30 && w_extent < (int64_t)1 << 30 &&
                     (int64_t)a.N * a.OH * a.OW < (int64_t)1 << 30;
@@ -65,16 +60,10 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
 
     double best_cost = 0.0;
     int best = -1;
-    if (k3) {
-        consider<V224x64>(a, &best_cost, &best, 0, g, lds);
-        consider<V224x32>(a, &best_cost, &best, 1, g, lds);
-        consider<V128x64>(a, &best_cost, &best, 2, g, lds);
-        consider<V64x64>(a, &best_cost, &best, 3, g, lds);
-    } else {
-        consider<P224x64>(a, &best_cost, &best, 4, g, lds);
-        consider<P224x32>(a, &best_cost, &best, 5, g, lds);
-        consider<P64x64>(a, &best_cost, &best, 6, g, lds);
-    }
+    consider<V224x64>(a, &best_cost, &best, 0, g, lds);
+    consider<V224x32>(a, &best_cost, &best, 1, g, lds);
+    consider<V128x64>(a, &best_cost, &best, 2, g, lds);
+    consider<V64x64>(a, &best_cost, &best, 3, g, lds);
     return best;
 }
 
@@ -120,10 +109,7 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
             if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
             return V224x32::launch(a, g, lds, stream);
         case 2: return V128x64::launch(a, g, lds, stream);
-        case 3: return V64x64::launch(a, g, lds, stream);
-        case 4: return P224x64::launch(a, g, lds, stream);
-        case 5: return P224x32::launch(a, g, lds, stream);
-        default: return P64x64::launch(a, g, lds, stream);
+        default: return V64x64::launch(a, g, lds, stream);
     }
 }
 
