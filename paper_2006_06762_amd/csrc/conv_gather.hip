@@ -42,11 +42,13 @@ bool make_plan(const ConvArgs& a, Plan* g, bool allow_taps = true)
     // 3 x 3 and 1 x 1 kernels whose channels fill whole chunks take the form with compile-time taps
     g->taps = 0;
     g->kc = KC;
+    // 7 x 7: one channel per chunk, its 49 taps padded to 52
+    if (allow_taps && a.R == 7 && a.S == 7) { g->taps = 49; g->kc = 52; }
     if (allow_taps && is_aligned16(a.w)) {
         if (a.R == 3 && a.S == 3 && g->Cg % 4 == 0) { g->taps = 9; g->kc = 36; }
         if (a.R == 1 && a.S == 1 && g->Cg % 32 == 0) { g->taps = 1; g->kc = 32; }
     }
-    g->nchunks = (g->Ktot + g->kc - 1) / g->kc;
+    g->nchunks = g->taps == 49 ? g->Cg : (g->Ktot + g->kc - 1) / g->kc;
     g->w_vec = (g->Ktot % 4 == 0) && is_aligned16(a.w);
     g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) &&
                    is_aligned16(a.y);
@@ -77,6 +79,8 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     g->Kpad = g->tiles_n * bn;
     g->d_tiles_m = make_fastdiv(g->tiles_m);
     g->d_tiles = make_fastdiv(g->tiles_m * g->tiles_n);
+    g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
+    g->d_rblocks = make_fastdiv(g->rblocks);
 }
 
 // Estimated run time in microseconds of tile t with the reduction split ks ways.  Two bounds:
@@ -244,13 +248,19 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     hipError_t err;
     if (g.taps) {
         if (g.bm != 64 || g.bn != 64) return hipErrorInvalidValue;
-        err = g.taps == 9 ? launch_tile_taps<64, 64, 3, 3>(a, g, stream) : launch_tile_taps<64, 64, 1, 1>(a, g, stream);
+        if (g.taps == 49) {
+            const size_t lds_bytes = sizeof(float) * (size_t)(64 + 64) * (g.kc + 2);
+            const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
+            err = launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g);
+        } else {
+            err = g.taps == 9 ? launch_tile_taps<64, 64, 3, 3>(a, g, stream)
+                              : launch_tile_taps<64, 64, 1, 1>(a, g, stream);
+        }
     } else if (g.bm == 128 && g.bn == 128) err = launch_tile<128, 128>(a, g, stream);
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);
     else err = launch_tile<64, 64>(a, g, stream);
     if (err != hipSuccess || g.ksplit == 1) return err;
-    const int64_t threads = (int64_t)a.K * (g.Mpad / 4) * kReduceLanes;
-    return launch_kernel(conv_splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+    return launch_kernel(conv_splitk_reduce_kernel, dim3((unsigned)((int64_t)a.K * g.rblocks)), dim3(256), 0, stream,
                          a, g);
 }
 

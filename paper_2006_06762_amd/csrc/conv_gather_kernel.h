@@ -53,7 +53,9 @@ struct Plan {
     FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles, d_tiles_ng, d_kg;
     int bm, bn;                  // chosen tile (host side)
     int kc;                      // reduction elements per chunk: KC, or 36 for the 3 x 3 form of conv_taps_kernel
-    int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1
+    int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1; 49: conv_bigtaps_kernel
+    int rblocks;                 // work-groups per output channel in the split-K reduction
+    FastDiv d_rblocks;
 };
 
 // Epilogue of one accumulator quad: registers 4q .. 4q+3 of a lane are pixels mq .. mq+3 of
@@ -514,6 +516,164 @@ __global__ __launch_bounds__(256) void conv_taps_kernel(const ConvArgs p, const 
     store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
 
+// Large kernels on few channels (the 7 x 7 stem of the shape lists: 3 channels, 49 taps): a chunk
+// is ONE input channel, its T taps padded to a multiple of four.  The four threads of a pixel
+// take taps akg, akg + 4, ...: which tap a load fetches is fixed for the thread, so its byte
+// offset (or the out-of-range marker where the tap leaves the image, and for the padding) sits
+// in a register and the channel rides in the scalar offset, as in conv_taps_kernel.  The general
+// kernel spends two thirds of its SIMD time on gather arithmetic for this layer.  Weight rows
+// are read as 16-byte units at 4-byte alignment (buffer loads of several dwords need dword
+// alignment only) plus single floats for the T % 4 taps left over, so nothing past a row's
+// chunk is ever multiplied.  One LDS buffer, two barriers per chunk, the next chunk's loads in
+// flight meanwhile: a work-group has only as many chunks as the layer has channels, and the
+// smaller footprint keeps four work-groups on a CU.
+template <int R_, int S_>
+__global__ __launch_bounds__(256) void conv_bigtaps_kernel(const ConvArgs p, const Plan g)
+{
+    constexpr int BM = 64, BN = 64;
+    constexpr int T = R_ * S_;
+    constexpr int KCT = (T + 3) / 4 * 4;            // reduction elements per chunk, padding included
+    constexpr int WST = KCT + 2;                    // LDS row stride, floats
+    constexpr int AU = KCT / 4;                     // A elements per thread and chunk
+    constexpr int FU = T / 4, REM = T % 4;          // whole 16-byte units and left-over floats per weight row
+    constexpr int BUNITS = BN * FU;
+    constexpr int BU = (BUNITS + 255) / 256;
+    constexpr int A_SZ = BM * WST;
+
+    extern __shared__ __attribute__((aligned(16))) float glds[];   // A[BM][WST], then B[BN][WST]
+    float* const lds_a = glds;
+    float* const lds_b = glds + A_SZ;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int split = g.d_tiles.div((int)blockIdx.x);
+    const int trem = (int)blockIdx.x - split * tiles;
+    const int tile_n = g.d_tiles_m.div(trem), tile_m = trem - tile_n * g.tiles_m;
+    const int grp = g.d_tiles_ng.div(tile_n);
+    const int m0 = tile_m * BM, cl0 = (tile_n - grp * g.tiles_ng) * BN;
+    const int cog = grp * g.Kg;
+    const int c_begin = split * g.chunks_per_split;
+    const int c_end = c_begin + g.chunks_per_split < g.nchunks ? c_begin + g.chunks_per_split : g.nchunks;
+
+    // ---- the pixel this thread gathers for and the byte offsets of its taps akg + 4 i
+    const int am = tid % BM;
+    const int akg = __builtin_amdgcn_readfirstlane(tid / BM);
+    uint32_t voff[AU];
+    {
+        int m = m0 + am;
+        m = m < g.Mtot ? m : g.Mtot - 1;      // rows past the end repeat the last pixel, never stored
+        const int gr = g.d_ow.div(m), ow = m - gr * p.OW;
+        const int n = g.d_oh.div(gr), oh = gr - n * p.OH;
+        const int ihb = oh * p.stride_h - p.pad_h, iwb = ow * p.stride_w - p.pad_w;
+        const int xbase = (int)(n * p.xs[0] + (int64_t)grp * g.Cg * p.xs[1] + ihb * p.xs[2] + iwb);
+        const int xs2 = (int)p.xs[2];
+#pragma unroll
+        for (int i = 0; i < AU; ++i) {
+            const int t = akg + 4 * i;            // uniform over the wave
+            const int r = t / S_, s = t - r * S_;
+            const bool ok = (t < T) & ((unsigned)(ihb + r * p.dil_h) < (unsigned)p.H) &
+                            ((unsigned)(iwb + s * p.dil_w) < (unsigned)p.W);
+            voff[i] = ok ? 4u * (uint32_t)(xbase + r * p.dil_h * xs2 + s * p.dil_w) : kOutOfRange;
+        }
+    }
+    // ---- weight units of this thread: unit u is floats 4q .. 4q+3 of the chunk of row u / FU;
+    //      slots past the tile's units duplicate an earlier one, columns past the group repeat its
+    //      last (never stored).  Left-over float e of row tid % BN goes to thread tid (e = tid / BN).
+    uint32_t wvoff[BU], wlds[BU];
+#pragma unroll
+    for (int j = 0; j < BU; ++j) {
+        const int u = (tid + 256 * j) % BUNITS;
+        const int row = u / FU, q = u - row * FU;
+        int co = cl0 + row;
+        co = cog + (co < g.Kg ? co : g.Kg - 1);
+        wvoff[j] = 4u * (uint32_t)(co * g.Ktot + 4 * q);
+        wlds[j] = (uint32_t)(row * WST + 4 * q);
+    }
+    uint32_t rvoff = 0, rlds = 0;
+    if (REM > 0) {
+        const int row = tid % BN, e = (tid / BN) % REM;
+        int co = cl0 + row;
+        co = cog + (co < g.Kg ? co : g.Kg - 1);
+        rvoff = 4u * (uint32_t)(co * g.Ktot + 4 * FU + e);
+        rlds = (uint32_t)(row * WST + 4 * FU + e);
+    }
+    // the padding columns of the weight tile are never written again; the pixel tile's are
+    // rewritten with the zeros its out-of-range loads return
+    if (KCT > T)
+        for (int i = tid; i < BN * (KCT - T); i += 256) lds_b[(i / (KCT - T)) * WST + T + i % (KCT - T)] = 0.f;
+
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
+    const int xs1 = (int)p.xs[1];
+
+    float ra[2][AU], rr[2];
+    f32x4 rb[2][BU];
+    auto load_chunk = [&](int c, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+#pragma unroll
+        for (int i = 0; i < AU; ++i)
+            ra[set][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)voff[i], 4 * c * xs1, 0));
+#pragma unroll
+        for (int j = 0; j < BU; ++j)
+            rb[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)wvoff[j], 4 * c * T, 0));
+        if (REM > 0)
+            rr[set] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, (int)rvoff, 4 * c * T, 0));
+    };
+    auto store_chunk = [&](auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        float* const a = lds_a + am * WST + akg;
+#pragma unroll
+        for (int i = 0; i < AU; ++i) a[4 * i] = ra[set][i];
+#pragma unroll
+        for (int j = 0; j < BU; ++j) {
+            f32x2* dst = reinterpret_cast<f32x2*>(lds_b + wlds[j]);
+            const f32x2 lo = {rb[set][j][0], rb[set][j][1]}, hi = {rb[set][j][2], rb[set][j][3]};
+            dst[0] = lo;
+            dst[1] = hi;
+        }
+        if (REM > 0) lds_b[rlds] = rr[set];
+    };
+
+    f32x16 acc[1][1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
+
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
+    // Iteration c: register set P holds chunk c; chunk c+1 is requested into set P^1 before
+    // chunk c is staged and multiplied.
+    auto iteration = [&](int c, auto par_c) {
+        constexpr int P = decltype(par_c)::value;
+        load_chunk(clampc(c + 1), std::integral_constant<int, P ^ 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        store_chunk(std::integral_constant<int, P>{});
+        __syncthreads();
+        const float* a = lds_a + (wm * 32 + r32) * WST + 2 * h;
+        const float* b = lds_b + (wn * 32 + r32) * WST + 2 * h;
+#pragma unroll
+        for (int j = 0; j < KCT / 4; ++j) {
+            const f32x2 av = *reinterpret_cast<const f32x2*>(a + 4 * j);
+            const f32x2 bv = *reinterpret_cast<const f32x2*>(b + 4 * j);
+            acc[0][0] = mfma32(av[0], bv[0], acc[0][0]);
+            acc[0][0] = mfma32(av[1], bv[1], acc[0][0]);
+        }
+        __syncthreads();                       // the tile is overwritten by the next chunk
+    };
+    load_chunk(c_begin, S0{});
+    for (int c = c_begin; c < c_end; c += 2) {
+        iteration(c, S0{});
+        if (c + 1 < c_end) iteration(c + 1, S1{});
+    }
+    store_tile<1, 1>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
+}
+
 // Sums the ksplit partial tiles and runs the epilogue.  Eight lanes share one (output channel,
 // four consecutive pixels): lane j adds the partials of splits j, j + 8, ... (all its loads in
 // flight at once), then the eight sums are combined by a fixed shuffle tree, so the result does
@@ -522,33 +682,33 @@ constexpr int kReduceLanes = 8;
 
 __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs p, const Plan g)
 {
-    const int mquads = g.Mpad >> 2;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t idx = gid / kReduceLanes;
-    const int sub = (int)(gid - idx * kReduceLanes);
-    int co = (int)(idx / mquads);
-    const int mq = 4 * (int)(idx - (int64_t)co * mquads);
-    const bool live = co < p.K && mq < g.Mtot;
-    co = co < p.K ? co : p.K - 1;                 // surplus lanes redo the last channel, store nothing
+    // a work-group stays inside one output channel (blocks_per_co of them per channel), so the
+    // channel, its workspace column and its batch-norm constants are scalar work
+    const int co = g.d_rblocks.div((int)blockIdx.x);
+    const int rblock = (int)blockIdx.x - co * g.rblocks;
+    const int t = rblock * 256 + (int)threadIdx.x;
+    const int sub = t & (kReduceLanes - 1);
+    const int mq = 4 * (t / kReduceLanes);
+    const bool live = mq < g.Mtot;
     // channel co sits in column (its group's first tile) * bn + (index inside the group)
     const int grp = g.d_kg.div(co);
-    const float* src = p.ws + ((int64_t)grp * g.tiles_ng * g.bn + (co - grp * g.Kg)) * g.Mpad + mq;
+    const float* src = p.ws + ((int64_t)grp * g.tiles_ng * g.bn + (co - grp * g.Kg)) * g.Mpad + (mq < g.Mpad ? mq : 0);
     const int64_t step = (int64_t)g.Kpad * g.Mpad;
     f32x4 v = zero4();
     int s = sub;
     for (; s + 3 * kReduceLanes < g.ksplit; s += 4 * kReduceLanes) {
-        f32x4 t[4];
+        f32x4 u[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = ldg4(src + (s + i * kReduceLanes) * step);
+        for (int i = 0; i < 4; ++i) u[i] = ldg4(src + (s + i * kReduceLanes) * step);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] += t[i][r];
+            for (int r = 0; r < 4; ++r) v[r] += u[i][r];
     }
     for (; s < g.ksplit; s += kReduceLanes) {
-        const f32x4 t = ldg4(src + s * step);
+        const f32x4 u = ldg4(src + s * step);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] += t[r];
+        for (int r = 0; r < 4; ++r) v[r] += u[r];
     }
 #pragma unroll
     for (int o = 1; o < kReduceLanes; o <<= 1)

@@ -92,7 +92,9 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const GemmArgs p, int ti
         } else {
             const int col = n0 + 4 * (tid % BQ);
             bcol_ok = col < N;                  // N is a multiple of 4: a unit is in or out as a whole
-            boff[j] = 4u * (uint32_t)((int64_t)(bk + (256 / BQ) * j) * p.ldb + (bcol_ok ? col : 0));
+            // a column past N keeps the out-of-range marker whatever is added to it for the chunk
+            // (extents are below 2^29 floats)
+            boff[j] = bcol_ok ? 4u * (uint32_t)((int64_t)(bk + (256 / BQ) * j) * p.ldb + col) : kOutOfRange;
         }
     }
 
@@ -100,22 +102,35 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const GemmArgs p, int ti
     auto load_chunk = [&](int chunk, auto set_c) {
         constexpr int set = decltype(set_c)::value;
         const int k0 = chunk * KC;
-        const bool a_in = k0 + ak < K;          // K is a multiple of 4
+        if (k0 + KC <= K) {
+            // a whole chunk: the chunk's part of the offset is uniform and rides in the scalar
+            // offset of the load, so no vector-ALU instruction sits between the MFMAs for it
+            // (each one costs the matrix pipe about eight cycles)
 #pragma unroll
-        for (int j = 0; j < AU; ++j) {
-            const uint32_t off = a_in ? aoff[j] + 4u * (uint32_t)k0 : kOutOfRange;
-            ra[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(arsrc, (int)off, 0, 0));
-        }
+            for (int j = 0; j < AU; ++j)
+                ra[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(arsrc, (int)aoff[j], 4 * k0, 0));
+            const int bs = NT ? 4 * k0 : 4 * k0 * p.ldb;
 #pragma unroll
-        for (int j = 0; j < BU; ++j) {
-            uint32_t off;
-            if (NT) {
-                off = a_in ? boff[j] + 4u * (uint32_t)k0 : kOutOfRange;
-            } else {
-                const bool in = bcol_ok && (k0 + bk + (256 / BQ) * j < K);
-                off = in ? boff[j] + 4u * (uint32_t)((int64_t)k0 * p.ldb) : kOutOfRange;
+            for (int j = 0; j < BU; ++j)
+                rb[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(brsrc, (int)boff[j], bs, 0));
+        } else {
+            const bool a_in = k0 + ak < K;          // K is a multiple of 4
+#pragma unroll
+            for (int j = 0; j < AU; ++j) {
+                const uint32_t off = a_in ? aoff[j] + 4u * (uint32_t)k0 : kOutOfRange;
+                ra[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(arsrc, (int)off, 0, 0));
             }
-            rb[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(brsrc, (int)off, 0, 0));
+#pragma unroll
+            for (int j = 0; j < BU; ++j) {
+                uint32_t off;
+                if (NT) {
+                    off = a_in ? boff[j] + 4u * (uint32_t)k0 : kOutOfRange;
+                } else {
+                    const bool in = k0 + bk + (256 / BQ) * j < K;
+                    off = in ? boff[j] + 4u * (uint32_t)((int64_t)k0 * p.ldb) : kOutOfRange;
+                }
+                rb[set][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(brsrc, (int)off, 0, 0));
+            }
         }
     };
     auto store_rows = [&](float* tile, const auto& reg) {

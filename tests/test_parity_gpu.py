@@ -628,6 +628,60 @@ def test_conv2d_random_geometries(anr):
         assert_parity(y, ref, exact=True, what="random conv %d %s" % (i, s))
 
 
+
+def _random_tap_shapes(count, seed):
+    """Geometries of the kernels with compile-time taps: 3x3 with channels per group a multiple of
+    4, 1x1 with a multiple of 32, 7x7 with any channel count; everything else random."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    while len(shapes) < count:
+        kind = int(g.choice([1, 3, 3, 7]))
+        groups = int(g.choice([1, 1, 2, 3]))
+        cg = {1: 32 * int(g.integers(1, 4)), 3: 4 * int(g.integers(1, 9)), 7: int(g.integers(1, 7))}[kind]
+        K = groups * int(g.integers(1, 90))
+        dil = (int(g.integers(1, 3)), int(g.integers(1, 3)))
+        stride = (int(g.integers(1, 3)), int(g.integers(1, 3)))
+        pad = (int(g.integers(0, 4)), int(g.integers(0, 4)))
+        H, W = int(g.integers(1, 30)), int(g.integers(1, 30))
+        s = I.ConvShape(int(g.integers(1, 4)), groups * cg, H, W, K, kind, kind, stride, pad, dil, groups)
+        if s.OH >= 1 and s.OW >= 1:
+            shapes.append(s)
+    return shapes
+
+
+def test_conv2d_random_geometries_tap_kernels(anr):
+    """Seeded random geometries for the 3x3 / 1x1 / 7x7 forms of the general kernel (whole-channel
+    chunks, one byte offset per tap), small-integer values, bit for bit; every third case passes its
+    weights at an address that is only 4-byte aligned (the 3x3 and 1x1 forms then hand over to the
+    any-geometry kernel, the 7x7 form reads its 16-byte units unaligned)."""
+    for i, s in enumerate(_random_tap_shapes(36, 950)):
+        x, w = I.conv_inputs(s, 951 + i, ints=True)
+        wd = dev(w)
+        if i % 3 == 2:
+            wbuf = torch.empty((wd.numel() + 1,), device="cuda")
+            wbuf[1:] = wd.reshape(-1)
+            wd = wbuf[1:].view(wd.shape)
+            assert wd.data_ptr() % 16 == 4
+        buf, y = guarded((s.N, s.K, s.OH, s.OW))
+        anr.conv2d(dev(x), wd, y, s.stride, s.pad, dil=s.dil, groups=s.groups)
+        check_guard(buf)
+        ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups)
+        assert_parity(y, ref, exact=True, what="random tap-kernel conv %d %s" % (i, s))
+
+
+def test_conv_bn_relu_stem_split_k(anr):
+    """7x7 stride-2 layer on a small image: the three channel chunks are split over work-groups and
+    the fused epilogue runs in the reduce kernel."""
+    s = I.ConvShape(1, 3, 40, 44, 64, 7, 7, (2, 2), (3, 3))
+    x, w = I.conv_inputs(s, 990)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 991)
+    buf, y = guarded((1, s.K, s.OH, s.OW))
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+    assert_parity(y, ref, what="7x7 ConvLayer")
+
+
 def test_conv2d_random_geometries_tuned_kernel(anr, monkeypatch):
     """Seeded random geometries inside what the tuned patch-staging kernel takes (3x3 with C % 8 == 0,
     1x1 with C % 32 == 0 and C >= 256, W % 4 == 0), forced onto it whatever the tile count."""
