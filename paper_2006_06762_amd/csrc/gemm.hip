@@ -262,20 +262,22 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* out, int64_t r
 // ---------------------------------------------------------------------------------------
 // Small problems (few output tiles, long K), e.g. the 512^3 GMM of the benchmark: 268 MFLOP
 // are 64 MFMAs per SIMD if and only if all 1024 SIMDs take part, so a work-group owns one
-// 32 x 32 tile of C and its four waves split K.  The waves share no operand; each stages its
-// own slices of A (32 rows x K/4) and B (K/4 x 32) through a private region of LDS purely to
-// turn fully coalesced 16-byte global loads (whole 128-byte lines, eight per instruction)
-// into the per-lane operand order of the MFMA: issuing the operand loads straight from
-// global memory costs 2.8 us of address-unit time for this shape, the staged form a third
-// of that.  All loads of a wave are in flight before its first MFMA.  The four partial
-// tiles meet in LDS once; every wave then sums and stores 8 rows.  Work-group ids are
-// mapped to tiles so that the 32 work-groups that land on one XCD (ids are dealt round-robin
-// over the 8 XCDs) form a compact block of C and share their panels of A and B in that
-// XCD's L2.
-// Phase timestamps (512^3): 1.6 us until the 32 loads of a lane are issued, 2.9 us of LDS
-// staging and MFMAs, 0.35 us reduction, 0.45 us store.  Issuing only the first two stages up
-// front and weaving the rest between the MFMAs moved time from the first phase to the second
-// and changed nothing overall; the first ~1 us is kernel start-up and first-access latency.
+// 32 x 32 tile of C and its NW waves split K, NST stages of 32 each (K = 128, 256, 512 run 4, 8,
+// 16 waves with one stage each).  The waves share no operand; each stages its own slices of A
+// (32 rows x 32 NST) and B (32 NST x 32) through a private region of LDS purely to turn fully
+// coalesced 16-byte global loads (whole 128-byte lines, eight per instruction) into the
+// per-lane operand order of the MFMA: issuing the operand loads straight from global memory
+// costs 2.8 us of address-unit time for this shape, the staged form a third of that.  All loads
+// of a wave are in flight before its first MFMA.  The partial tiles meet in LDS once; every
+// wave then sums and stores 16 / NW accumulator registers.  Work-group ids are mapped to tiles
+// so that the 32 work-groups that land on one XCD (ids are dealt round-robin over the 8 XCDs)
+// form a compact block of C and share their panels of A and B in that XCD's L2.
+// The kernel is a chain of latencies (start-up and first access ~1 us, load issue, one memory
+// round trip, LDS staging, MFMAs, reduction, store), not a throughput problem: with four waves
+// of four stages each (512^3) the phases took 1.6 + 2.9 + 0.35 + 0.45 us; sixteen waves of one
+// stage put four waves on every SIMD, so one wave's staging overlaps another's MFMAs and each
+// wave issues 8 loads instead of 32: 6.5 -> 5.8 us cold.  Weaving the later stages' loads
+// between the MFMAs of the four-stage form had changed nothing.
 #ifdef ANR_GEMM_TRACE
 __device__ long long* anr_gemm_trace = nullptr;
 #define GT(slot) do { if (threadIdx.x == 0 && anr_gemm_trace) anr_gemm_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
@@ -288,11 +290,12 @@ __device__ long long* anr_gemm_trace = nullptr;
 constexpr int kKsLd = 36;                       // LDS row stride (floats) of a 32-wide stage
 constexpr int kKsStage = 2 * 32 * kKsLd;        // floats per stage: A block then B block
 
-template <int NST>
-__global__ __launch_bounds__(256) void gemm_tile32_ksplit_kernel(const GemmArgs p, int tiles_m, int tiles_n,
-                                                                 int xcd_map)
+template <int NST, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_tile32_ksplit_kernel(const GemmArgs p, int tiles_m, int tiles_n,
+                                                                     int xcd_map)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // [4 waves][NST][kKsStage]
+    static_assert(16 % NW == 0, "a wave finishes 16 / NW accumulator registers");
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // [NW waves][NST][kKsStage]
     GT(0);
 
     const int tid = threadIdx.x;
@@ -372,30 +375,31 @@ __global__ __launch_bounds__(256) void gemm_tile32_ksplit_kernel(const GemmArgs 
     for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r] + acc2[r];
     __syncthreads();
     GT(3);
-    // wave w finishes accumulator registers 4w .. 4w+3: rows 8w + 4h + q of the tile
+    // wave w finishes accumulator registers (16 / NW) w ...: register r is row 8 (r / 4) + 4 h + r % 4
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = wave * 4 + q;
-        const float v = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
-                        red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
-        C[(int64_t)(tm * 32 + 8 * wave + 4 * h + q) * p.ldc + tn * 32 + r32] = v;
+    for (int q = 0; q < 16 / NW; ++q) {
+        const int r = wave * (16 / NW) + q;
+        float v = 0.f;
+#pragma unroll
+        for (int o = 0; o < NW; ++o) v += red[(o * 16 + r) * 64 + lane];
+        C[(int64_t)(tm * 32 + 8 * (r / 4) + 4 * h + (r % 4)) * p.ldc + tn * 32 + r32] = v;
     }
     GT_END(4);
 }
 
-template <int NST>
+template <int NST, int NW>
 hipError_t launch_ksplit(const GemmArgs& a, hipStream_t stream)
 {
     const int tiles_m = a.M / 32, tiles_n = a.N / 32;
-    const size_t lds_bytes = sizeof(float) * 4 * NST * kKsStage;
-    auto kern = gemm_tile32_ksplit_kernel<NST>;
+    const size_t lds_bytes = sizeof(float) * NW * NST * kKsStage;
+    auto kern = gemm_tile32_ksplit_kernel<NST, NW>;
     if (lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
     const int xcd_map = (tiles_m % 4 == 0) && (tiles_n % 2 == 0);
-    return launch_kernel(kern, dim3(tiles_m * tiles_n, 1, a.batch), dim3(256), lds_bytes, stream, a, tiles_m,
+    return launch_kernel(kern, dim3(tiles_m * tiles_n, 1, a.batch), dim3(64 * NW), lds_bytes, stream, a, tiles_m,
                          tiles_n, xcd_map);
 }
 
@@ -454,8 +458,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream)
     if (!a.b_is_nk && !a.softmax_rows && (a.M % 32 == 0) && (a.N % 32 == 0) && tiles32 <= 1024 &&
         a.batch_inner == 1 && is_aligned16(a.A) && is_aligned16(a.B) && (a.lda % 4 == 0) && (a.ldb % 4 == 0) &&
         (a.sAo % 4 == 0) && (a.sBo % 4 == 0) && a.batch <= 65535) {
-        if (a.K == 256) return launch_ksplit<2>(a, stream);
-        if (a.K == 512) return launch_ksplit<4>(a, stream);
+        if (a.K == 128) return launch_ksplit<1, 4>(a, stream);
+        if (a.K == 256) return launch_ksplit<1, 8>(a, stream);
+        if (a.K == 512) return launch_ksplit<1, 16>(a, stream);
     }
 
     hipError_t err;

@@ -117,6 +117,33 @@ def test_gemm_pipelined_tiles(anr, M, N, K, batch, ints):
     assert_parity(C, oracle.gemm(A, B), exact=ints, what="gemm %dx%dx%d b%d" % (M, N, K, batch))
 
 
+@pytest.mark.parametrize("M,N,K,batch", [(64, 96, 128, 1), (32, 32, 256, 1), (96, 160, 256, 3), (160, 64, 512, 2),
+                                         (32, 512, 512, 1), (256, 256, 128, 4)])
+@pytest.mark.parametrize("ints", [False, True])
+def test_gemm_wave_split_k_tiles(anr, M, N, K, batch, ints):
+    """Few 32x32 tiles and K of 128, 256 or 512: one tile per work-group, its 4, 8 or 16 waves split K."""
+    A, B = I.gemm_inputs(I.GemmShape(M, N, K, batch), 120 + K, ints=ints)
+    shape = (batch, M, N) if batch > 1 else (M, N)
+    buf, C = guarded(shape)
+    anr.gemm(dev(A), dev(B), C)
+    check_guard(buf)
+    assert_parity(C, oracle.gemm(A, B), exact=ints, what="gemm %dx%dx%d b%d" % (M, N, K, batch))
+
+
+def test_gemm_wave_split_k_strided_views(anr):
+    """The same kernel on views into wider matrices (leading dimensions that are multiples of 4)."""
+    A, B = I.gemm_inputs(I.GemmShape(64, 96, 256), 131)
+    Aw = torch.zeros((64, 264), device="cuda")
+    Bw = torch.zeros((256, 104), device="cuda")
+    Cw = torch.full((64, 100), CANARY, device="cuda")
+    Aw[:, 4:260] = dev(A)
+    Bw[:, 8:104] = dev(B)
+    anr.gemm(Aw[:, 4:260], Bw[:, 8:104], Cw[:, 1:97])
+    assert_parity(Cw[:, 1:97].contiguous(), oracle.gemm(A, B), what="strided split-K gemm")
+    Cw[:, 1:97] = CANARY
+    assert bool((Cw == CANARY).all()), "store outside the output view"
+
+
 def test_gemm_identity_returns_a(anr):
     A, _ = I.gemm_inputs(I.GemmShape(96, 96, 96), 9)
     C = torch.empty((96, 96), device="cuda")
