@@ -31,6 +31,41 @@ hipError_t launch_rows_s2(const ConvArgs& a, hipStream_t stream)
                          a, lpr, ppw, planes, row_chunks);
 }
 
+// Small planes of dense tensors: see dwconv_small_planes_kernel.
+hipError_t launch_small_planes(const ConvArgs& a, hipStream_t stream, bool* taken)
+{
+    *taken = false;
+    const int64_t hw = (int64_t)a.H * a.W, ohw = (int64_t)a.OH * a.OW;
+    const bool dense = a.xs[2] == a.W && a.xs[1] == hw && a.xs[0] == a.C * hw && a.ys[2] == a.OW && a.ys[1] == ohw &&
+                       a.ys[0] == a.C * ohw && is_aligned16(a.x) && is_aligned16(a.y);
+    // at most about eight outputs per thread, ranges that start 16-byte aligned, and at least three
+    // work-groups per CU where the tensor has that many planes
+    const int64_t planes = (int64_t)a.N * a.C;
+    int G = (int)(2048 / ohw) & ~3;
+    if (G > 256) G = 256;
+    if (!dense || G == 0 || a.C >= (1 << 30)) return hipSuccess;
+    const int64_t spread = (planes / 768) & ~(int64_t)3;
+    if (spread < G) G = spread < 4 ? 4 : (int)spread;
+    const int64_t rs = (int64_t)a.R * a.S;
+    const int64_t lds_floats = ((G * hw + 3) & ~(int64_t)3) + ((G * ohw + 3) & ~(int64_t)3) + G * rs;
+    if (lds_floats * 4 > 48 * 1024 || planes >= ((int64_t)1 << 31) || (planes + G - 1) / G >= ((int64_t)1 << 31))
+        return hipSuccess;
+    dw::SmallPlanes g;
+    g.G = G;
+    g.hw = (int)hw;
+    g.ohw = (int)ohw;
+    g.rs = (int)rs;
+    g.planes = planes;
+    g.d_ohw = make_fastdiv((int)ohw);
+    g.d_ow = make_fastdiv(a.OW);
+    g.d_c = make_fastdiv(a.C);
+    *taken = true;
+    const dim3 grid((unsigned)((planes + G - 1) / G));
+    if (a.R == 3 && a.S == 3)
+        return launch_kernel(dw::dwconv_small_planes_kernel<3, 3>, grid, dim3(256), (size_t)lds_floats * 4, stream, a, g);
+    return launch_kernel(dw::dwconv_small_planes_kernel<0, 0>, grid, dim3(256), (size_t)lds_floats * 4, stream, a, g);
+}
+
 }  // namespace
 
 hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken)
@@ -59,6 +94,8 @@ hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream)
 {
     bool taken = false;
     hipError_t err = launch_dwconv3x3(a, stream, &taken);
+    if (taken || err != hipSuccess) return err;
+    err = launch_small_planes(a, stream, &taken);
     if (taken || err != hipSuccess) return err;
     return launch_dwconv_direct(a, stream);
 }

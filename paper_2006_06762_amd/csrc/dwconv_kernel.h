@@ -133,5 +133,99 @@ __global__ __launch_bounds__(64 * WPB) void dwconv3x3s2_kernel(const ConvArgs p,
     }
 }
 
+// Small planes (14 x 14 and 7 x 7 maps of the MobileNet shape list, any kernel, stride, padding
+// and dilation) of dense NCHW tensors: a work-group takes G consecutive planes, which are one
+// contiguous range of x and of y.  The range is copied to LDS with coalesced 16-byte loads, the
+// outputs are computed from LDS into LDS and leave as coalesced 16-byte stores.  With one thread per output reading x through the vector caches,
+// 7x7x1024 at batch 16 took 9.8 us for 6.4 MB; a plane's nine-fold tap reuse belongs in LDS.
+struct SmallPlanes {
+    int G;              // planes per work-group (a multiple of 4: ranges start 16-byte aligned)
+    int hw, ohw;        // H*W, OH*OW
+    int rs;             // R*S
+    int64_t planes;     // N*C
+    FastDiv d_ohw, d_ow, d_c;
+};
+
+template <int R_, int S_>     // kernel size, or 0, 0 for any
+__global__ __launch_bounds__(256) void dwconv_small_planes_kernel(const ConvArgs p, const SmallPlanes g)
+{
+    extern __shared__ __attribute__((aligned(16))) float dlds[];   // x[G*hw], y[G*ohw], w[G*rs]
+    float* const lx = dlds;
+    float* const ly = dlds + ((g.G * g.hw + 3) & ~3);
+    float* const lw = ly + ((g.G * g.ohw + 3) & ~3);
+
+    const int tid = threadIdx.x;
+    const int64_t plane0 = (int64_t)blockIdx.x * g.G;
+    const int nplanes = g.planes - plane0 < g.G ? (int)(g.planes - plane0) : g.G;
+
+    // ---- planes plane0 .. plane0 + nplanes - 1: nplanes * hw contiguous floats of x
+    {
+        const float* __restrict__ src = p.x + plane0 * g.hw;
+        const int count = nplanes * g.hw;
+        for (int i = 4 * tid; i < count; i += 4 * 256) {
+            if (i + 3 < count) {
+                *reinterpret_cast<f32x4*>(lx + i) = ldg4(src + i);
+            } else {
+                for (int e = i; e < count; ++e) lx[e] = src[e];
+            }
+        }
+        for (int i = tid; i < nplanes * g.rs; i += 256) {
+            const int pl = i / g.rs, t = i - pl * g.rs;
+            const int64_t plane = plane0 + pl;
+            const int c = (int)(plane - (int64_t)g.d_c.div((int)plane) * p.C);
+            lw[i] = p.w[(int64_t)c * g.rs + t];
+        }
+    }
+    __syncthreads();
+
+    // ---- a thread computes outputs tid, tid + 256, ...; with the kernel size known at compile time
+    //      the taps of an output are unrolled, so its LDS reads are in flight together (one output
+    //      row per thread with run-time loops waited for each of its 63 reads in turn: 3 us)
+    {
+        const int count = nplanes * g.ohw;
+        for (int o = tid; o < count; o += 256) {
+            const int pl = g.d_ohw.div(o), pix = o - pl * g.ohw;
+            const int oh = g.d_ow.div(pix), ow = pix - oh * p.OW;
+            const float* xin = lx + pl * g.hw;
+            const float* wt = lw + pl * g.rs;
+            const int ih0 = oh * p.stride_h - p.pad_h, iw0 = ow * p.stride_w - p.pad_w;
+            float acc = 0.f;
+            if (R_ > 0) {
+#pragma unroll
+                for (int r = 0; r < R_; ++r)
+#pragma unroll
+                    for (int s = 0; s < S_; ++s) {
+                        const int ih = ih0 + r * p.dil_h, iw = iw0 + s * p.dil_w;
+                        const bool ok = ((unsigned)ih < (unsigned)p.H) & ((unsigned)iw < (unsigned)p.W);
+                        const float v = xin[ok ? ih * p.W + iw : 0];
+                        acc = fmaf(ok ? v : 0.f, wt[r * S_ + s], acc);
+                    }
+            } else {
+                for (int r = 0; r < p.R; ++r)
+                    for (int s = 0; s < p.S; ++s) {
+                        const int ih = ih0 + r * p.dil_h, iw = iw0 + s * p.dil_w;
+                        if (((unsigned)ih < (unsigned)p.H) & ((unsigned)iw < (unsigned)p.W))
+                            acc = fmaf(xin[ih * p.W + iw], wt[r * p.S + s], acc);
+                    }
+            }
+            ly[o] = acc;
+        }
+    }
+    __syncthreads();
+
+    // ---- nplanes * ohw contiguous floats of y
+    {
+        float* __restrict__ dst = p.y + plane0 * g.ohw;
+        const int count = nplanes * g.ohw;
+        for (int i = 4 * tid; i < count; i += 4 * 256) {
+            if (i + 3 < count) {
+                stg4(dst + i, *reinterpret_cast<const f32x4*>(ly + i));
+            } else {
+                for (int e = i; e < count; ++e) dst[e] = ly[e];
+            }
+        }
+    }
+}
+
 }  // namespace dw
 }  // namespace anr

@@ -471,6 +471,19 @@ def test_dwconv_small(anr, shape, ints):
     assert_parity(y, oracle.dwconv(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
 
 
+def test_dwconv_small_planes_many_planes(anr):
+    """Small maps with enough planes that a work-group stages several of them through LDS, the last
+    work-group with fewer (plane count not a multiple of the group); 3x3 and a 5x2 kernel."""
+    for s in [I.ConvShape(2, 3101, 7, 7, 3101, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(1, 6150, 14, 14, 6150, 3, 3, (2, 2), (1, 1)),
+              I.ConvShape(3, 2051, 6, 5, 2051, 5, 2, (1, 2), (2, 0))]:
+        x, w = I.dwconv_inputs(s, 470, ints=True)
+        buf, y = guarded((s.N, s.C, s.OH, s.OW))
+        anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+        check_guard(buf)
+        assert_parity(y, oracle.dwconv(x, w, s.stride, s.pad), exact=True, what=str(s))
+
+
 def test_dwconv_config(anr):
     cfg = I.config_inputs("DEP")
     s = cfg["shape"]
