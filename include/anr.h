@@ -21,12 +21,14 @@
  *     results.
  *   - `ws`/`ws_bytes` is a device workspace owned by the caller, 16-byte
  *     aligned.  anr_workspace_size() says how many bytes an operation may
- *     want for a descriptor; ws may be NULL when that is 0.  Only the
- *     convolutions use one, and only for shapes with few output tiles and a
- *     long reduction (batch 1, 7x7 maps), whose reduction is split over
- *     work-groups that leave partial tiles there; its contents on entry do
- *     not matter and are undefined on return.  A call that needs more than
- *     it is given returns ANR_ERR_WORKSPACE.  Calls that share one workspace
+ *     want for a descriptor (a figure that depends on the descriptor only,
+ *     not on pointer alignment); ws may be NULL when that is 0.  Two
+ *     operations use one: the convolutions for shapes with few output tiles
+ *     and a long reduction (batch 1, 7x7 maps), whose reduction is split
+ *     over work-groups that leave partial tiles there, and anr_nrm for the
+ *     partial sums of a matrix's slices.  Its contents on entry do not
+ *     matter and are undefined on return.  A call that needs more than it
+ *     is given returns ANR_ERR_WORKSPACE.  Calls that share one workspace
  *     must be ordered (same stream).
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is launched, so an invalid call has no effect on the device.
