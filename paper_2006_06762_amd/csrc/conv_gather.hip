@@ -79,6 +79,15 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     g->Kpad = g->tiles_n * bn;
     g->d_tiles_m = make_fastdiv(g->tiles_m);
     g->d_tiles = make_fastdiv(g->tiles_m * g->tiles_n);
+    // conv_taps_kernel: with at most one work-group per CU and a long chain of chunks, two or four
+    // groups of waves share the chain (measured: 196 work-groups x 16 chunks 18.3 -> 16.9 us, x 32
+    // chunks 27.7 -> 24.3 us; with more work-groups per CU or short chains the larger work-groups
+    // only cost occupancy)
+    g->nwg = 1;
+    if ((g->taps == 9 || g->taps == 1) && (int64_t)g->tiles_m * g->tiles_n * g->ksplit <= kCUs) {
+        if (g->chunks_per_split >= 32) g->nwg = 4;
+        else if (g->chunks_per_split >= 8) g->nwg = 2;
+    }
     g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
     g->d_rblocks = make_fastdiv(g->rblocks);
 }
@@ -196,18 +205,26 @@ hipError_t launch_tile_as(const ConvArgs& a, const Plan& g, hipStream_t stream)
     return launch_kernel(kern, dim3(grid), dim3(256), lds_bytes, stream, a, g);
 }
 
-template <int BM, int BN, int R_, int S_>
+template <int BM, int BN, int R_, int S_, int NWG>
 hipError_t launch_tile_taps(const ConvArgs& a, const Plan& g, hipStream_t stream)
 {
-    const size_t lds_bytes = sizeof(float) * 2 * (size_t)(BM + BN) * (g.kc + 2);
-    auto kern = conv_taps_kernel<BM, BN, R_, S_>;
+    const size_t lds_bytes = sizeof(float) * NWG * 2 * (size_t)(BM + BN) * (g.kc + 2);
+    auto kern = conv_taps_kernel<BM, BN, R_, S_, NWG>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
     const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
-    return launch_kernel(kern, dim3(grid), dim3(256), lds_bytes, stream, a, g);
+    return launch_kernel(kern, dim3(grid), dim3(256 * NWG), lds_bytes, stream, a, g);
+}
+
+template <int R_, int S_>
+hipError_t launch_taps_groups(const ConvArgs& a, const Plan& g, hipStream_t stream)
+{
+    if (g.nwg == 4) return launch_tile_taps<64, 64, R_, S_, 4>(a, g, stream);
+    if (g.nwg == 2) return launch_tile_taps<64, 64, R_, S_, 2>(a, g, stream);
+    return launch_tile_taps<64, 64, R_, S_, 1>(a, g, stream);
 }
 
 template <int BM, int BN>
@@ -253,8 +270,7 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
             const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
             err = launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g);
         } else {
-            err = g.taps == 9 ? launch_tile_taps<64, 64, 3, 3>(a, g, stream)
-                              : launch_tile_taps<64, 64, 1, 1>(a, g, stream);
+            err = g.taps == 9 ? launch_taps_groups<3, 3>(a, g, stream) : launch_taps_groups<1, 1>(a, g, stream);
         }
     } else if (g.bm == 128 && g.bn == 128) err = launch_tile<128, 128>(a, g, stream);
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);

@@ -54,6 +54,7 @@ struct Plan {
     int bm, bn;                  // chosen tile (host side)
     int kc;                      // reduction elements per chunk: KC, or 36 for the 3 x 3 form of conv_taps_kernel
     int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1; 49: conv_bigtaps_kernel
+    int nwg;                     // conv_taps_kernel: groups of four waves per work-group (1, 2 or 4)
     int rblocks;                 // work-groups per output channel in the split-K reduction
     FastDiv d_rblocks;
 };
@@ -360,8 +361,14 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 // On this hardware every vector-ALU instruction of any wave on a SIMD takes about eight cycles
 // from the matrix pipe, and counters show the general kernel above spending 35-40 % of its
 // SIMD time on them.  Weights: a chunk of a row is KC consecutive floats of the OIHW order.
-template <int BM, int BN, int R_, int S_>
-__global__ __launch_bounds__(256) void conv_taps_kernel(const ConvArgs p, const Plan g)
+//
+// NWG > 1: the work-group has NWG groups of four waves; group w takes every NWG-th chunk of the
+// work-group's range through staging buffers of its own, and the groups' accumulators meet in LDS
+// at the end.  For launches with one work-group per CU (batch 1: the chain of a work-group's
+// chunks is what takes the time, and the matrix pipes idle between its barriers) this shortens the
+// chain NWG-fold without more partial tiles in the workspace.
+template <int BM, int BN, int R_, int S_, int NWG>
+__global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, const Plan g)
 {
     constexpr int T = R_ * S_;
     constexpr int CPC = T == 1 ? 32 : 4;            // channels per chunk
@@ -376,12 +383,15 @@ __global__ __launch_bounds__(256) void conv_taps_kernel(const ConvArgs p, const 
     constexpr int BU = (BUNITS + 255) / 256;        // B units per thread and chunk
     constexpr int A_SZ = BM * WST, B_SZ = BN * WST;
     static_assert(KCT % 4 == 0 && CPC % KG == 0, "chunk geometry");
+    static_assert(NWG == 1 || (MB == 1 && NB == 1), "wave groups share 64 x 64 tiles only");
+    constexpr int REGION = 2 * (A_SZ + B_SZ);       // floats of staging per wave group
 
-    extern __shared__ __attribute__((aligned(16))) float glds[];   // A[2][BM][WST], then B[2][BN][WST]
-    float* const lds_a = glds;
-    float* const lds_b = glds + 2 * A_SZ;
+    extern __shared__ __attribute__((aligned(16))) float glds[];   // per group: A[2][BM][WST], then B[2][BN][WST]
+    const int wgrp = NWG > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    float* const lds_a = glds + wgrp * REGION;
+    float* const lds_b = lds_a + 2 * A_SZ;
 
-    const int tid = threadIdx.x;
+    const int tid = (int)threadIdx.x & 255;         // thread inside its wave group
     const int lane = tid & 63, wave = tid >> 6;
     const int r32 = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
@@ -476,42 +486,66 @@ __global__ __launch_bounds__(256) void conv_taps_kernel(const ConvArgs p, const 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
+    // chunks past the end of the range are the last chunk again: loaded, never multiplied (no
+    // branch around the loads)
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
 
-    load_chunk(c_begin, S0{});
-    load_chunk(clampc(c_begin + 1), S1{});
+    // this group's chunks: first, first + NWG, ...; every group runs the same number of iterations
+    // (the barriers are the work-group's)
+    const int first = c_begin + wgrp;
+    const int iters = (c_end - c_begin + NWG - 1) / NWG;
+    load_chunk(clampc(first), S0{});
+    load_chunk(clampc(first + NWG), S1{});
     store_chunk(0, S0{});
     __syncthreads();
 
-    // Iteration c: LDS buffer P holds chunk c, register set P^1 chunk c+1, set P is free.
+    // Iteration c: LDS buffer P holds chunk c, register set P^1 the group's next chunk, set P is free.
     auto iteration = [&](int c, auto par_c) {
         constexpr int P = decltype(par_c)::value;
-        load_chunk(clampc(c + 2), std::integral_constant<int, P>{});
+        load_chunk(clampc(c + 2 * NWG), std::integral_constant<int, P>{});
         __builtin_amdgcn_sched_barrier(0);
         const float* a = lds_a + P * A_SZ + (wm * MB * 32 + r32) * WST + 2 * h;
         const float* b = lds_b + P * B_SZ + (wn * NB * 32 + r32) * WST + 2 * h;
+        if (NWG == 1 || c < c_end) {          // a group may have one chunk fewer than the others
 #pragma unroll
-        for (int j = 0; j < KCT / 4; ++j) {
-            f32x2 av[MB], bv[NB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WST + 4 * j);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WST + 4 * j);
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
+            for (int j = 0; j < KCT / 4; ++j) {
+                f32x2 av[MB], bv[NB];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
+                    av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WST + 4 * j);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
+                for (int nb = 0; nb < NB; ++nb)
+                    bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WST + 4 * j);
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
+            }
         }
         store_chunk(P ^ 1, std::integral_constant<int, P ^ 1>{});
         __syncthreads();
     };
-    for (int c = c_begin; c < c_end; c += 2) {
-        iteration(c, S0{});
-        if (c + 1 < c_end) iteration(c + 1, S1{});
+    for (int i = 0; i < iters; i += 2) {
+        iteration(first + i * NWG, S0{});
+        if (i + 1 < iters) iteration(first + (i + 1) * NWG, S1{});
+    }
+    if (NWG > 1) {
+        // the last iteration ended with a barrier: every staging region is free.  Groups 1 .. NWG-1
+        // leave their accumulators in their own regions, group 0 adds them in group order.
+        if (wgrp > 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lds_a[(wave * 16 + r) * 64 + lane] = acc[0][0][r];
+        }
+        __syncthreads();
+        if (wgrp > 0) return;
+#pragma unroll
+        for (int o = 1; o < NWG; ++o)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][0][r] += glds[o * REGION + (wave * 16 + r) * 64 + lane];
     }
     store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }

@@ -709,6 +709,21 @@ def test_conv2d_random_geometries_tap_kernels(anr):
         assert_parity(y, ref, exact=True, what="random tap-kernel conv %d %s" % (i, s))
 
 
+def test_conv2d_wave_groups_share_a_chain(anr):
+    """About 200 output tiles with 16 and with 32 chunks each and no split-K: the work-groups of
+    the compile-time-tap kernel then run two and four groups of waves that take alternate chunks
+    and add their accumulators in LDS."""
+    for s in [I.ConvShape(4, 64, 56, 56, 64, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(8, 1024, 14, 14, 512, 1, 1, (1, 1), (0, 0)),
+              I.ConvShape(2, 36, 40, 40, 100, 3, 3, (1, 1), (1, 1), (2, 2), 1)]:
+        x, w = I.conv_inputs(s, 995, ints=True)
+        buf, y = guarded((s.N, s.K, s.OH, s.OW))
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil, groups=s.groups)
+        check_guard(buf)
+        ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups)
+        assert_parity(y, ref, exact=True, what=str(s))
+
+
 def test_conv_bn_relu_stem_split_k(anr):
     """7x7 stride-2 layer on a small image: the three channel chunks are split over work-groups and
     the fused epilogue runs in the reduce kernel."""
