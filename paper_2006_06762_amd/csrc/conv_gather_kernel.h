@@ -59,13 +59,20 @@ struct Plan {
     FastDiv d_rblocks;
 };
 
+// Inference batch norm of output channel co as one multiply-add: y = v * scale + shift.
+__device__ __forceinline__ void bn_constants(const ConvArgs& p, int co, float* scale, float* shift)
+{
+    *scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
+    *shift = p.beta[co] - p.mean[co] * *scale;
+}
+
 // Epilogue of one accumulator quad: registers 4q .. 4q+3 of a lane are pixels mq .. mq+3 of
-// output channel co.
-__device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v)
+// output channel co; scale and shift are that channel's batch-norm constants (used when the
+// call has a fused epilogue).
+__device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v, float scale,
+                                           float shift)
 {
     if (p.gamma) {
-        const float scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
-        const float shift = p.beta[co] - p.mean[co] * scale;
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = fmaxf(fmaf(v[r], scale, shift), 0.f);
     }
@@ -99,21 +106,26 @@ __device__ __forceinline__ void store_tile(const ConvArgs& p, const Plan& g, con
     float* const wsp = p.ws + ((int64_t)split * g.Kpad + tile_n * BN + wn * NB * 32 + r32) * g.Mpad + m0 +
                        wm * MB * 32 + 4 * h;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int nb = 0; nb < NB; ++nb) {
+        const int tcol = (wn * NB + nb) * 32 + r32;             // column inside the tile: one channel per lane
+        const bool col_ok = cl0 + tcol < g.Kg;
+        // the channel's batch-norm constants once per lane, not once per quad (the division and
+        // square root are a dozen vector-ALU instructions each time)
+        float scale = 1.f, shift = 0.f;
+        if (g.ksplit == 1 && p.gamma && col_ok) bn_constants(p, cog + cl0 + tcol, &scale, &shift);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int tcol = (wn * NB + nb) * 32 + r32;             // column inside the tile
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const f32x4 v = {acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
                                  acc[mb][nb][4 * q + 3]};
                 if (g.ksplit > 1) {
                     stg4(wsp + (int64_t)(nb * 32) * g.Mpad + mb * 32 + 8 * q, v);
-                } else if (cl0 + tcol < g.Kg) {
-                    store_quad(p, g, m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h, cog + cl0 + tcol, v);
+                } else if (col_ok) {
+                    store_quad(p, g, m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h, cog + cl0 + tcol, v, scale, shift);
                 }
             }
-        }
+    }
 }
 
 // MASK: the kernel has at most 31 taps, so which taps of a pixel fall outside the image fits one
@@ -748,7 +760,11 @@ __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs 
     for (int o = 1; o < kReduceLanes; o <<= 1)
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] += __shfl_xor(v[r], o);
-    if (live && sub == 0) store_quad(p, g, mq, co, v);
+    if (live && sub == 0) {
+        float scale = 1.f, shift = 0.f;
+        if (p.gamma) bn_constants(p, co, &scale, &shift);
+        store_quad(p, g, mq, co, v, scale, shift);
+    }
 }
 
 }  // namespace gconv
