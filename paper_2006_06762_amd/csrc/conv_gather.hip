@@ -42,13 +42,14 @@ bool make_plan(const ConvArgs& a, Plan* g, bool allow_taps = true)
     // 3 x 3 and 1 x 1 kernels whose channels fill whole chunks take the form with compile-time taps
     g->taps = 0;
     g->kc = KC;
-    // 7 x 7: one channel per chunk, its 49 taps padded to 52
+    // 7 x 7 and 5 x 5: one channel per chunk, its 49 (25) taps padded to 52 (28)
     if (allow_taps && a.R == 7 && a.S == 7) { g->taps = 49; g->kc = 52; }
+    if (allow_taps && a.R == 5 && a.S == 5) { g->taps = 25; g->kc = 28; }
     if (allow_taps && is_aligned16(a.w)) {
         if (a.R == 3 && a.S == 3 && g->Cg % 4 == 0) { g->taps = 9; g->kc = 36; }
         if (a.R == 1 && a.S == 1 && g->Cg % 32 == 0) { g->taps = 1; g->kc = 32; }
     }
-    g->nchunks = g->taps == 49 ? g->Cg : (g->Ktot + g->kc - 1) / g->kc;
+    g->nchunks = g->taps >= 25 ? g->Cg : (g->Ktot + g->kc - 1) / g->kc;
     g->w_vec = (g->Ktot % 4 == 0) && is_aligned16(a.w);
     g->vec_store = (g->ohow % 4 == 0) && a.ys[2] == a.OW && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) &&
                    is_aligned16(a.y);
@@ -265,10 +266,11 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     hipError_t err;
     if (g.taps) {
         if (g.bm != 64 || g.bn != 64) return hipErrorInvalidValue;
-        if (g.taps == 49) {
+        if (g.taps >= 25) {
             const size_t lds_bytes = sizeof(float) * (size_t)(64 + 64) * (g.kc + 2);
             const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
-            err = launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g);
+            err = g.taps == 49 ? launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g)
+                               : launch_kernel(conv_bigtaps_kernel<5, 5>, dim3(grid), dim3(256), lds_bytes, stream, a, g);
         } else {
             err = g.taps == 9 ? launch_taps_groups<3, 3>(a, g, stream) : launch_taps_groups<1, 1>(a, g, stream);
         }

@@ -53,7 +53,7 @@ struct Plan {
     FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles, d_tiles_ng, d_kg;
     int bm, bn;                  // chosen tile (host side)
     int kc;                      // reduction elements per chunk: KC, or 36 for the 3 x 3 form of conv_taps_kernel
-    int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1; 49: conv_bigtaps_kernel
+    int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1; 49 or 25: conv_bigtaps_kernel
     int nwg;                     // conv_taps_kernel: groups of four waves per work-group (1, 2 or 4)
     int rblocks;                 // work-groups per output channel in the split-K reduction
     FastDiv d_rblocks;
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, 
     store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
 
-// Large kernels on few channels (the 7 x 7 stem of the shape lists: 3 channels, 49 taps): a chunk
+// Large kernels (7 x 7 and 5 x 5; the 7 x 7 stem of the shape lists has 3 channels, 49 taps): a chunk
 // is ONE input channel, its T taps padded to a multiple of four.  The four threads of a pixel
 // take taps akg, akg + 4, ...: which tap a load fetches is fixed for the thread, so its byte
 // offset (or the out-of-range marker where the tap leaves the image, and for the padding) sits

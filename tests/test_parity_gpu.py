@@ -671,13 +671,14 @@ def test_conv2d_random_geometries(anr):
 
 def _random_tap_shapes(count, seed):
     """Geometries of the kernels with compile-time taps: 3x3 with channels per group a multiple of
-    4, 1x1 with a multiple of 32, 7x7 with any channel count; everything else random."""
+    4, 1x1 with a multiple of 32, 5x5 and 7x7 with any channel count; everything else random."""
     g = np.random.Generator(np.random.PCG64(seed))
     shapes = []
     while len(shapes) < count:
-        kind = int(g.choice([1, 3, 3, 7]))
+        kind = int(g.choice([1, 3, 3, 5, 7]))
         groups = int(g.choice([1, 1, 2, 3]))
-        cg = {1: 32 * int(g.integers(1, 4)), 3: 4 * int(g.integers(1, 9)), 7: int(g.integers(1, 7))}[kind]
+        cg = {1: 32 * int(g.integers(1, 4)), 3: 4 * int(g.integers(1, 9)), 5: int(g.integers(1, 9)),
+              7: int(g.integers(1, 7))}[kind]
         K = groups * int(g.integers(1, 90))
         dil = (int(g.integers(1, 3)), int(g.integers(1, 3)))
         stride = (int(g.integers(1, 3)), int(g.integers(1, 3)))
@@ -690,11 +691,11 @@ def _random_tap_shapes(count, seed):
 
 
 def test_conv2d_random_geometries_tap_kernels(anr):
-    """Seeded random geometries for the 3x3 / 1x1 / 7x7 forms of the general kernel (whole-channel
+    """Seeded random geometries for the 3x3 / 1x1 / 5x5 / 7x7 forms of the general kernel (whole-channel
     chunks, one byte offset per tap), small-integer values, bit for bit; every third case passes its
     weights at an address that is only 4-byte aligned (the 3x3 and 1x1 forms then hand over to the
-    any-geometry kernel, the 7x7 form reads its 16-byte units unaligned)."""
-    for i, s in enumerate(_random_tap_shapes(36, 950)):
+    any-geometry kernel, the 5x5 / 7x7 form reads its 16-byte units unaligned)."""
+    for i, s in enumerate(_random_tap_shapes(48, 950)):
         x, w = I.conv_inputs(s, 951 + i, ints=True)
         wd = dev(w)
         if i % 3 == 2:
