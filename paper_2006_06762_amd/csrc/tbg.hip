@@ -65,7 +65,16 @@ hipError_t launch_tbg(const GemmArgs& a, hipStream_t stream)
         if (a.M <= 64) return launch_tbs_by_d<2>(t, a.batch, vec_store, stream);
         return launch_tbs_by_d<4>(t, a.batch, vec_store, stream);
     }
-    hipError_t err = launch_kernel(tbg::tbg_tile_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t);
+    // whole tiles, whole chunks and 32-bit byte offsets inside one (b, h) view: the lean form
+    const bool whole = (a.M % tbg::kTile == 0) && (a.K % tbg::kChunk == 0) &&
+                       (int64_t)(a.M - 1) * a.lda + a.K < ((int64_t)1 << 29) &&
+                       (int64_t)(a.N - 1) * a.ldb + a.K < ((int64_t)1 << 29) &&
+                       (int64_t)(a.M - 1) * a.ldc + a.N < ((int64_t)1 << 29);
+    t.d_tiles_j = make_fastdiv(t.tiles_j);
+    t.d_tiles_i = make_fastdiv(t.tiles_i);
+    t.d_h = make_fastdiv(t.H);
+    hipError_t err = whole ? launch_kernel(tbg::tbg_tile64_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t)
+                           : launch_kernel(tbg::tbg_tile_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t);
     if (err != hipSuccess || !a.softmax_rows) return err;
     return launch_softmax_rows(a, stream);
 }

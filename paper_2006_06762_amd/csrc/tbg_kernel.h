@@ -40,6 +40,7 @@ struct Args {
     int64_t os_b, os_h, os_i;   // element strides of out [b, h, i, j] (j stride 1)
     int tiles_i, tiles_j;       // ceil(S / 64) each
     int xcd_chunk;              // tiles per XCD when the tile count is a multiple of 8, else 0
+    FastDiv d_tiles_j, d_tiles_i, d_h;   // divisors tiles_j, tiles_i, H (tbg_tile64_kernel)
 };
 
 #ifdef ANR_TBG_TRACE
@@ -134,6 +135,90 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
         }
     }
     TT_END(4);
+}
+
+// The same tile for whole tiles and whole chunks (S and D multiples of 64: every shape of the
+// paper's list) with the address arithmetic taken out of the vector ALU.  Counted on the kernel
+// above, a wave spent about as many cycles on vector-ALU instructions (64-bit addresses of 8
+// loads and 16 stores, bounds, the tile index's divisions, two accumulators to initialise and
+// add) as on its 32 MFMAs, and with three waves per SIMD that is matrix time lost.  Here a lane
+// holds one byte offset per operand and one for the output; tile, row group and chunk ride in
+// the scalar offset of buffer loads and stores; one accumulator (consecutive MFMAs on one
+// accumulator do not stall on this hardware).
+__global__ __launch_bounds__(256) void tbg_tile64_kernel(const Args p)
+{
+    __shared__ __attribute__((aligned(16))) float qs[kTile * kLds];
+    __shared__ __attribute__((aligned(16))) float ks[kTile * kLds];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, h2 = lane >> 5;
+    int t = blockIdx.x;
+    if (p.xcd_chunk > 0) t = (t & 7) * p.xcd_chunk + (t >> 3);
+    int q1 = p.d_tiles_j.div(t);
+    const int tj = t - q1 * p.tiles_j;
+    int q2 = p.d_tiles_i.div(q1);
+    const int ti = q1 - q2 * p.tiles_i;
+    const int b = p.d_h.div(q2), hh = q2 - b * p.H;
+    const int i0 = ti * kTile, j0 = tj * kTile;
+
+    const float* qb = p.q + b * p.qs_b + hh * p.qs_h;
+    const float* kb = p.k + b * p.ks_b + hh * p.ks_h;
+    float* ob = p.out + b * p.os_b + hh * p.os_h;
+    const int qs_s = (int)p.qs_s, ks_s = (int)p.ks_s, os_i = (int)p.os_i;
+    const __amdgpu_buffer_rsrc_t qrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(qb), 0, 4 * ((p.S - 1) * qs_s + p.D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(kb), 0, 4 * ((p.S - 1) * ks_s + p.D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+        ob, 0, 4 * ((p.S - 1) * os_i + p.S), 0x00020000);
+
+    // staging: thread -> (row = tid / 16 + 16*u, 16 bytes at d = 4 * (tid % 16)), u = 0..3
+    const int srow = tid >> 4, sd = (tid & 15) * 4;
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;   // this wave's 32 x 32 block
+    const int voffq = 4 * (srow * qs_s + sd), voffk = 4 * (srow * ks_s + sd);
+
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    for (int d0 = 0; d0 < p.D; d0 += kChunk) {
+        f32x4 rq[4], rk[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            rq[u] = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(qrsrc, voffq, 4 * ((i0 + 16 * u) * qs_s + d0), 0));
+            rk[u] = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(krsrc, voffk, 4 * ((j0 + 16 * u) * ks_s + d0), 0));
+        }
+        if (d0 > 0) __syncthreads();             // previous chunk fully consumed
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            *reinterpret_cast<f32x4*>(&qs[(srow + 16 * u) * kLds + sd]) = rq[u];
+            *reinterpret_cast<f32x4*>(&ks[(srow + 16 * u) * kLds + sd]) = rk[u];
+        }
+        __syncthreads();
+
+        f32x4 a[8], bb[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            a[kk] = *reinterpret_cast<const f32x4*>(&qs[(wi + r32) * kLds + kk * 8 + 4 * h2]);
+            bb[kk] = *reinterpret_cast<const f32x4*>(&ks[(wj + r32) * kLds + kk * 8 + 4 * h2]);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc = mfma32(a[kk][e], bb[kk][e], acc);
+    }
+
+    // register r of lane (h2, r32): row 8*(r/4) + 4*h2 + r%4, column r32 of the block
+    const int voffo = 4 * ((wi + 4 * h2) * os_i + wj + r32);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float v = acc[r];
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), orsrc, voffo,
+                                              4 * ((i0 + 8 * (r / 4) + (r % 4)) * os_i + j0), 0);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
