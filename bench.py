@@ -383,7 +383,7 @@ def main():
             traffic = None
     # the kernel behind each operator's benchmark launch (with --only, the roofline is that operator's)
     kernels = {"GMM": "gemm_tile32_ksplit_kernel", "C2D": "conv_igemm_kernel", "ConvLayer": "conv_igemm_kernel",
-               "C2D_S2": "conv_igemm_kernel", "TBG": "tbg_tile_kernel", "TBS": "tbs_rows32_kernel",
+               "C2D_S2": "conv_igemm_kernel", "TBG": "tbg_tile64_kernel", "TBS": "tbs_rows32_kernel",
                "DEP": "dwconv3x3_kernel"}
     if dom["bound"] == "hbm":
         roofline = {

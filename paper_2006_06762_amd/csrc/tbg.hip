@@ -17,7 +17,17 @@ hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipS
     // q rows, then the k panel, which the staged probabilities (rows_q x ldp) later overwrite
     const size_t kpanel = (size_t)T::rows_k * ld, probs = (size_t)T::rows_q * T::ldp;
     const size_t lds_bytes = sizeof(float) * ((size_t)T::rows_q * ld + (kpanel > probs ? kpanel : probs));
-    auto kern = tbg::tbs_rows32_kernel<UT, true, KB>;
+    t.d_tiles_i = make_fastdiv(t.tiles_i);
+    t.d_h = make_fastdiv(t.H);
+    // the whole form: S is exactly the keys of KB blocks and whole blocks of queries, D whole
+    // chunks, 32-bit byte offsets inside one (b, h) view
+    constexpr bool whole_ut = UT == (T::rows_q + T::rows_k) / 16;
+    const bool whole = whole_ut && t.S == T::rows_k && (t.S % T::rows_q == 0) && (t.D % tbg::kChunk == 0) &&
+                       (int64_t)(t.S - 1) * t.qs_s + t.D < ((int64_t)1 << 29) &&
+                       (int64_t)(t.S - 1) * t.ks_s + t.D < ((int64_t)1 << 29) &&
+                       (int64_t)(t.S - 1) * t.os_i + t.S < ((int64_t)1 << 29);
+    constexpr int UTW = (T::rows_q + T::rows_k) / 16;
+    auto kern = whole ? tbg::tbs_rows32_kernel<UTW, true, KB, true> : tbg::tbs_rows32_kernel<UT, true, KB, false>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

@@ -26,6 +26,8 @@
 namespace anr {
 namespace tbg {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kTile = 64;            // output tile edge
 constexpr int kChunk = 64;           // reduction elements staged per pass
 constexpr int kLds = kChunk + 4;     // LDS row stride in floats (272 B: 16-byte reads stay conflict free)
@@ -253,7 +255,15 @@ struct TbsShape {
     static constexpr int ldp = rows_k + 4;        // row stride of the staged probabilities
 };
 
-template <int UT, bool SOFTMAX, int KB>
+//
+// WHOLE: S == 32 * KB, a multiple of the work-group's query rows, and D a multiple of 64 (every
+// shape of the paper's list).  Nothing is then
+// clamped or masked, a thread's staging units are whole q units followed by whole k units, and
+// the loads are buffer loads with one byte offset per unit in a register and the chunk in the
+// scalar offset; the tile index is decoded with multiply-shift divisions.  Vector-ALU
+// instructions of any wave on a SIMD cost matrix time (about eight cycles each), and the general
+// form spends more of them on addresses than the softmax needs.
+template <int UT, bool SOFTMAX, int KB, bool WHOLE>
 __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, int vec_store)
 {
     using T = TbsShape<KB>;
@@ -272,9 +282,18 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     // tiles of one head, which all read its k panel, meet in one L2 (31.6 -> 12.7 MB fetched).
     int item = blockIdx.x;
     if (p.xcd_chunk > 0) item = (item & 7) * p.xcd_chunk + (item >> 3);
-    const int ti = item % p.tiles_i;
-    const int bh = item / p.tiles_i;
-    const int hh = bh % p.H, b = bh / p.H;
+    int ti, bh, hh, b;
+    if (WHOLE) {
+        bh = p.d_tiles_i.div(item);
+        ti = item - bh * p.tiles_i;
+        b = p.d_h.div(bh);
+        hh = bh - b * p.H;
+    } else {
+        ti = item % p.tiles_i;
+        bh = item / p.tiles_i;
+        hh = bh % p.H;
+        b = bh / p.H;
+    }
     const int i0 = ti * kRowsQ;
 
     const float* __restrict__ qb = p.q + b * p.qs_b + hh * p.qs_h;
@@ -292,27 +311,54 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     f32x4 rg[UT];
     const float* rowp[UT];
     int lds_off[UT], ucol[UT];
-#pragma unroll
-    for (int u = 0; u < UT; ++u) {
-        const int row = srow < rows_all ? srow : rows_all - 1;      // surplus units repeat the last row
-        const bool isq = row < kRowsQ;
-        // rows past S re-read row S-1; what they produce is masked or never stored
-        int gr = isq ? i0 + row : row - kRowsQ;
-        gr = gr < p.S ? gr : p.S - 1;
-        rowp[u] = isq ? qb + gr * p.qs_s : kb + gr * p.ks_s;
-        ucol[u] = 4 * scol;
-        lds_off[u] = row * ld + 4 * scol;
-        srow += row_step;
-        scol += col_step;
-        if (scol >= dq) { scol -= dq; ++srow; }
-    }
-    auto load_chunk = [&](int d0) {
+    // WHOLE: 16 units per row, 16 rows per pass of the work-group; units 0 .. UQ-1 are q rows,
+    // the rest k rows
+    constexpr int UQ = kRowsQ / 16;
+    uint32_t voff[UT];
+    const __amdgpu_buffer_rsrc_t qrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(qb), 0, WHOLE ? 4 * ((p.S - 1) * (int)p.qs_s + p.D) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(kb), 0, WHOLE ? 4 * ((p.S - 1) * (int)p.ks_s + p.D) : 0, 0x00020000);
+    if (WHOLE) {
+        static_assert(!WHOLE || UT == (kRowsQ + kRowsK) / 16, "whole form: 16 units per row");
+        const int r16 = tid >> 4, c16 = (tid & 15) * 4;
 #pragma unroll
         for (int u = 0; u < UT; ++u) {
-            // columns past D (last chunk of a D that is not a multiple of 64) repeat the last four;
-            // they land in LDS columns the MFMA loop does not read
-            const int col = d0 + ucol[u] < p.D ? d0 + ucol[u] : p.D - 4;
-            rg[u] = ldg4(rowp[u] + col);
+            const int row = r16 + 16 * u;                          // row of the panel: q rows, then k rows
+            voff[u] = u < UQ ? 4u * (uint32_t)((i0 + row) * (int)p.qs_s + c16)
+                             : 4u * (uint32_t)((row - kRowsQ) * (int)p.ks_s + c16);
+            lds_off[u] = row * ld + c16;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+            const int row = srow < rows_all ? srow : rows_all - 1;      // surplus units repeat the last row
+            const bool isq = row < kRowsQ;
+            // rows past S re-read row S-1; what they produce is masked or never stored
+            int gr = isq ? i0 + row : row - kRowsQ;
+            gr = gr < p.S ? gr : p.S - 1;
+            rowp[u] = isq ? qb + gr * p.qs_s : kb + gr * p.ks_s;
+            ucol[u] = 4 * scol;
+            lds_off[u] = row * ld + 4 * scol;
+            srow += row_step;
+            scol += col_step;
+            if (scol >= dq) { scol -= dq; ++srow; }
+        }
+    }
+    auto load_chunk = [&](int d0) {
+        if (WHOLE) {
+#pragma unroll
+            for (int u = 0; u < UT; ++u)
+                rg[u] = __builtin_bit_cast(
+                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(u < UQ ? qrsrc : krsrc, (int)voff[u], 4 * d0, 0));
+        } else {
+#pragma unroll
+            for (int u = 0; u < UT; ++u) {
+                // columns past D (last chunk of a D that is not a multiple of 64) repeat the last four;
+                // they land in LDS columns the MFMA loop does not read
+                const int col = d0 + ucol[u] < p.D ? d0 + ucol[u] : p.D - 4;
+                rg[u] = ldg4(rowp[u] + col);
+            }
         }
     };
     auto store_chunk = [&]() {
@@ -323,23 +369,23 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     store_chunk();
     __syncthreads();
 
-    f32x16 acc, acc2;
+    // one accumulator: consecutive MFMAs on one accumulator do not stall on this hardware
+    f32x16 mm;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
+    for (int r = 0; r < 16; ++r) mm[r] = 0.f;
     const float* arow = ks + (32 * wave + r32) * ld + 4 * h2;
     const float* brow = qs + (32 * qblk + r32) * ld + 4 * h2;
     for (int d0 = 0; d0 < p.D; d0 += kChunk) {
         const bool more = d0 + kChunk < p.D;             // uniform
         if (more) load_chunk(d0 + kChunk);
         __builtin_amdgcn_sched_barrier(0);               // keep the loads ahead of the MFMAs
-        const int width = p.D - d0 < kChunk ? p.D - d0 : kChunk;
+        const int width = WHOLE ? kChunk : (p.D - d0 < kChunk ? p.D - d0 : kChunk);
+#pragma unroll
         for (int d = 0; d < width; d += 8) {             // D is a multiple of 8
             const f32x4 a = *reinterpret_cast<const f32x4*>(arow + d);
             const f32x4 bq = *reinterpret_cast<const f32x4*>(brow + d);
-            acc = mfma32(a[0], bq[0], acc);
-            acc2 = mfma32(a[1], bq[1], acc2);
-            acc = mfma32(a[2], bq[2], acc);
-            acc2 = mfma32(a[3], bq[3], acc2);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mm = mfma32(a[e], bq[e], mm);
         }
         if (more) {
             __syncthreads();                             // every wave is done with this chunk
@@ -347,8 +393,10 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
             __syncthreads();
         }
     }
+    // the softmax works on ordinary registers (the matrix accumulator stays where the MFMAs left it)
+    float acc[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
+    for (int r = 0; r < 16; ++r) acc[r] = mm[r];
 
     // register r of lane (h2, r32): key 32*wave + 8*(r/4) + 4*h2 + r%4, query i0 + 32*qblk + r32
     const int key0 = 32 * wave + 4 * h2;
@@ -356,7 +404,7 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const bool in = key0 + 8 * (r / 4) + (r % 4) < p.S;
+            const bool in = WHOLE || key0 + 8 * (r / 4) + (r % 4) < p.S;
             acc[r] = in ? acc[r] : -INFINITY;
             mx = fmaxf(mx, acc[r]);
         }
@@ -368,9 +416,12 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
 #pragma unroll
         for (int w = 1; w < KB; ++w) mx = fmaxf(mx, red[0][qblk][w][r32]);
         float sum = 0.f;
+        // exp(s - mx) = 2^(s * log2(e) - mx * log2(e)): one multiply-add and one exponential per score
+        constexpr float kLog2e = 1.44269504088896340736f;
+        const float nmx = -mx * kLog2e;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            acc[r] = __expf(acc[r] - mx);                // exp(-inf) = 0 for masked keys
+            acc[r] = __builtin_amdgcn_exp2f(fmaf(acc[r], kLog2e, nmx));     // 2^(-inf) = 0 for masked keys
             sum += acc[r];
         }
         sum += __shfl_xor(sum, 32);
@@ -400,14 +451,29 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
     float* __restrict__ ob = p.out + b * p.os_b + hh * p.os_h;
     constexpr int LPR = 8 * KB, RPI = 64 / LPR;
     const int col = 4 * (lane % LPR);
+    if (WHOLE && vec_store) {
+        // buffer stores: the lane's row inside an instruction and its column in a register, the
+        // instruction's first row in the scalar offset
+        const int os_i = (int)p.os_i;
+        const __amdgpu_buffer_rsrc_t orsrc =
+            __builtin_amdgcn_make_buffer_rsrc(ob, 0, 4 * ((p.S - 1) * os_i + p.S), 0x00020000);
+        const int voffo = 4 * ((lane / LPR) * os_i + col);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rl = 8 * QBK * wv + RPI * i;            // uniform over the wave
+            const f32x4 v = *reinterpret_cast<const f32x4*>(&ps[(rl + lane / LPR) * kLdP + col]);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), orsrc, voffo, 4 * (i0 + rl) * os_i, 0);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int rl = 8 * QBK * wv + RPI * i + lane / LPR;
         const int row = i0 + rl;
         const f32x4 v = *reinterpret_cast<const f32x4*>(&ps[rl * kLdP + col]);
-        if (row < p.S) {
+        if (WHOLE || row < p.S) {
             float* orow = ob + row * p.os_i;
-            if (vec_store && col + 3 < p.S) {
+            if (vec_store && (WHOLE || col + 3 < p.S)) {
                 stg4(orow + col, v);
             } else {
 #pragma unroll
