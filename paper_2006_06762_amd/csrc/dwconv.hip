@@ -14,9 +14,10 @@ hipError_t launch_rows(const ConvArgs& a, hipStream_t stream)
     const int64_t planes = (int64_t)a.N * a.C;
     const int row_chunks = (a.OH + ROWS - 1) / ROWS;
     const int64_t waves = ((planes + ppw - 1) / ppw) * row_chunks;
+    const dw::RowDivs dv{make_fastdiv(row_chunks), make_fastdiv(lpr), make_fastdiv(a.C)};
     // A partly filled last work-group still runs: its surplus waves see plane >= planes.
     return launch_kernel(dwconv3x3_kernel<ROWS>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, stream,
-                         a, lpr, ppw, planes, row_chunks);
+                         a, lpr, ppw, planes, row_chunks, dv);
 }
 
 template <int ROWS>
@@ -27,8 +28,9 @@ hipError_t launch_rows_s2(const ConvArgs& a, hipStream_t stream)
     const int64_t planes = (int64_t)a.N * a.C;
     const int row_chunks = (a.OH + ROWS - 1) / ROWS;
     const int64_t waves = ((planes + ppw - 1) / ppw) * row_chunks;
+    const dw::RowDivs dv{make_fastdiv(row_chunks), make_fastdiv(lpr), make_fastdiv(a.C)};
     return launch_kernel(dw::dwconv3x3s2_kernel<ROWS>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, stream,
-                         a, lpr, ppw, planes, row_chunks);
+                         a, lpr, ppw, planes, row_chunks, dv);
 }
 
 // Small planes of dense tensors: see dwconv_small_planes_kernel.
@@ -72,7 +74,9 @@ hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
     const bool common = a.R == 3 && a.S == 3 && a.dil_h == 1 && a.dil_w == 1 && a.pad_h == 1 && a.pad_w == 1 &&
                         is_aligned16(a.x) && is_aligned16(a.y) && (a.xs[0] % 4 == 0) && (a.xs[1] % 4 == 0) &&
-                        (a.xs[2] % 4 == 0) && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) && (a.ys[2] % 4 == 0);
+                        (a.xs[2] % 4 == 0) && (a.ys[0] % 4 == 0) && (a.ys[1] % 4 == 0) && (a.ys[2] % 4 == 0) &&
+                        // wave and plane indices are divided as 31-bit numbers
+                        (int64_t)a.N * a.C * a.OH < ((int64_t)1 << 31);
     const bool s2 = common && a.stride_h == 2 && a.stride_w == 2 && (a.W % 8 == 0) && a.W <= 512;
     if (s2) {
         *taken = true;

@@ -16,21 +16,28 @@
 namespace anr {
 namespace dw {
 
+// divisors of the row kernels: row chunks per plane group, lanes per row, channels
+struct RowDivs {
+    FastDiv row_chunks, lanes_per_row, channels;
+};
+
 template <int ROWS, int WPB = 4>
 __global__ __launch_bounds__(64 * WPB) void dwconv3x3_kernel(const ConvArgs p, int lanes_per_row,
                                                         int planes_per_wave, int64_t planes,
-                                                        int row_chunks)
+                                                        int row_chunks, RowDivs dv)
 {
+    // wave, plane and channel indices by multiply-shift (the launch keeps them below 2^31): the
+    // 64-bit divisions they replace were some 300 vector-ALU instructions ahead of the first load
     const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-    const int64_t pgroup = wave / row_chunks;
-    const int oh0 = (int)(wave % row_chunks) * ROWS;
+    const int wave = __builtin_amdgcn_readfirstlane((int)blockIdx.x * WPB + (int)(threadIdx.x >> 6));
+    const int pgroup = dv.row_chunks.div(wave);
+    const int oh0 = (wave - pgroup * row_chunks) * ROWS;
 
-    const int pl = lane / lanes_per_row, ch = lane % lanes_per_row;
-    const int64_t plane = pgroup * planes_per_wave + pl;
+    const int pl = dv.lanes_per_row.div(lane), ch = lane - pl * lanes_per_row;
+    const int64_t plane = (int64_t)pgroup * planes_per_wave + pl;
     const bool active = (pl < planes_per_wave) && (plane < planes);
-    const int n = active ? (int)(plane / p.C) : 0;
-    const int c = active ? (int)(plane % p.C) : 0;
+    const int n = active ? dv.channels.div((int)plane) : 0;
+    const int c = active ? (int)plane - n * p.C : 0;
     const float* __restrict__ xp = p.x + n * p.xs[0] + c * p.xs[1] + 4 * ch;
     float* __restrict__ yp = p.y + n * p.ys[0] + c * p.ys[1] + 4 * ch;
     const bool first = ch == 0, last = ch == lanes_per_row - 1;
@@ -79,19 +86,19 @@ __global__ __launch_bounds__(64 * WPB) void dwconv3x3_kernel(const ConvArgs p, i
 template <int ROWS, int WPB = 4>
 __global__ __launch_bounds__(64 * WPB) void dwconv3x3s2_kernel(const ConvArgs p, int lanes_per_row,
                                                           int planes_per_wave, int64_t planes,
-                                                          int row_chunks)
+                                                          int row_chunks, RowDivs dv)
 {
     constexpr int IN = 2 * ROWS + 1;
     const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-    const int64_t pgroup = wave / row_chunks;
-    const int oh0 = (int)(wave % row_chunks) * ROWS;
+    const int wave = __builtin_amdgcn_readfirstlane((int)blockIdx.x * WPB + (int)(threadIdx.x >> 6));
+    const int pgroup = dv.row_chunks.div(wave);
+    const int oh0 = (wave - pgroup * row_chunks) * ROWS;
 
-    const int pl = lane / lanes_per_row, ch = lane % lanes_per_row;
-    const int64_t plane = pgroup * planes_per_wave + pl;
+    const int pl = dv.lanes_per_row.div(lane), ch = lane - pl * lanes_per_row;
+    const int64_t plane = (int64_t)pgroup * planes_per_wave + pl;
     const bool active = (pl < planes_per_wave) && (plane < planes);
-    const int n = active ? (int)(plane / p.C) : 0;
-    const int c = active ? (int)(plane % p.C) : 0;
+    const int n = active ? dv.channels.div((int)plane) : 0;
+    const int c = active ? (int)plane - n * p.C : 0;
     const float* __restrict__ xp = p.x + n * p.xs[0] + c * p.xs[1] + 8 * ch;
     float* __restrict__ yp = p.y + n * p.ys[0] + c * p.ys[1] + 4 * ch;
     const bool first = ch == 0;
