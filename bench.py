@@ -199,8 +199,10 @@ def shape_list(anr, I, torch):
                     else:
                         mk = lambda: (rnd(s.N, s.C, s.H, s.W), rnd(s.K, cin, s.R, s.S) * 0.05, emp(s.N, s.K, s.OH, s.OW))
                         run = lambda t: anr.conv2d(t[0], t[1], t[2], s.stride, s.pad, dil=s.dil, groups=s.groups)
-                # enough buffer sets that a launch does not find its data in the 256 MB Infinity Cache
-                nsets = int(min(12, max(2, -(-320e6 // nbytes))))
+                # enough buffer sets that a launch does not find its data in the 256 MB Infinity Cache:
+                # 600 MB in rotation where 24 sets reach that (at 300 MB the cache still served part of
+                # a 25 MB operator); the small shapes stay cache-resident whatever the count
+                nsets = int(min(24, max(2, -(-600e6 // nbytes))))
                 sets = [mk() for _ in range(nsets)]
                 for t in sets:
                     run(t)
@@ -327,9 +329,10 @@ def main():
     host = {name: I.config_inputs(name) for name in I.CONFIG_NAMES}
     names = I.CONFIG_NAMES if args.only is None else (args.only,)
 
-    # one step touches ~117 MB; 4 rotating sets keep a step from finding its data in the
-    # 256 MB Infinity Cache, 12 sets do the same for a single small operator
-    NSETS = 12
+    # one step touches ~135 MB; 4 rotating sets keep a step from finding its data in the
+    # 256 MB Infinity Cache.  A single operator's tensors are ~25 MB: with 12 sets (300 MB) the
+    # cache still served part of them (TBG 8.5 us against 9.1 us with 24 or 48 sets), so 24
+    NSETS = 24
     sets = [OpSet(anr, I, torch, host) for _ in range(NSETS)]
 
     def step(i):
