@@ -7,15 +7,16 @@ all inputs resident in HBM.  Prints ONE JSON line:
 
   value      whole-step fp32 throughput in TFLOP/s (sum of the operators' algorithmic
              FLOPs / step time), buffers rotated between steps so that a step does not
-             find its inputs in the 256 MB Infinity Cache of the previous one;
+             find its inputs in the 256 MB Infinity Cache of the previous one; the K timed
+             steps are replayed from a HIP graph of up to 48 steps (--eager: issued from Python);
   per_op     every operator's own launch time (HIP events on the launch stream around a
-             replayed HIP graph of 24 launches), warm (same buffers) and cold (12 rotating
+             replayed HIP graph of 48 launches), warm (same buffers) and cold (24 rotating
              buffer sets), TFLOP/s against the 157.3 TFLOP/s fp32 MFMA peak and GB/s
              against 8 TB/s; us_cold_eager is the same launch issued from Python;
   roofline   the dominant kernel (the implicit-GEMM convolution on its largest launch);
   cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample.
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--eager]
 """
 import argparse
 import json
@@ -282,6 +283,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing and parity check (profiling runs)")
+    ap.add_argument("--eager", action="store_true",
+                    help="issue every timed step from Python instead of replaying a HIP graph of steps")
     ap.add_argument("--only", default=None, help="profiling aid: launch only this operator in the step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
@@ -343,11 +346,38 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    # The timed K steps.  Several kernels of a step run 6-9 us, less than it takes Python to issue
+    # a launch, so the GPU waits for the host now and then (about 2.5 % of a step).  By default
+    # the steps are therefore captured in a HIP graph of up to 48 steps (a multiple of the 4
+    # rotating buffer sets) that is replayed K // G times, the remaining K % G steps issued one by
+    # one on the same stream; --eager issues all K steps from Python.
+    group = 0 if args.eager else (min(args.steps, 48) // 4) * 4
+    if group:
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(group):
+                    step(i)
+            graph.replay()                       # untimed: uploads the graph
+            stream.synchronize()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps // group):
+                graph.replay()
+            for i in range(args.steps % group):
+                step(i)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+        torch.cuda.current_stream().wait_stream(stream)
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1000.0 / args.steps
     step_flops = sum(table[n][0] for n in names)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
@@ -411,7 +441,8 @@ def main():
                                "3x3+BN+ReLU + TBG B16 S128 H12 D64 + DEP N16 C256 28^2 3x3 + C2D N16 256->512 "
                                "28^2 3x3 s2 (all BASELINE configs, fp32)" if args.only is None
                    else "only " + args.only,
-                   "step_gflop": step_flops / 1e9, "buffer_sets_rotated": 4},
+                   "step_gflop": step_flops / 1e9, "buffer_sets_rotated": 4,
+                   "steps_per_graph_replay": group},
         "roofline": roofline,
         "peaks": {"mfma_f32_tflops": PEAK_MFMA_F32_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
         "per_op": per_op,
