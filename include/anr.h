@@ -189,6 +189,29 @@ anr_status anr_nrm(const anr_nrm_desc *desc, const float *x, float *out,
  * the same way the operation does. */
 anr_status anr_workspace_size(int op, const void *desc, size_t *bytes);
 
+/* Which kernel anr_conv2d / anr_conv_bn_relu would run for `desc` with 16-byte aligned
+ * pointers, and how (host-side planning only: nothing is launched, no GPU is needed).  For
+ * callers that want to know why a layer takes the time it does, and for tests of the
+ * selection logic.  tile_m x tile_n is the work-group's output tile (pixels x channels),
+ * ksplit the number of work-groups that share a tile's reduction through the workspace,
+ * wave_groups the groups of four waves inside a work-group that share its chunk chain. */
+enum {
+    ANR_CONV_KERNEL_PATCH = 1,     /* 3x3 patch-staging kernel tuned on the ResNet-style layers   */
+    ANR_CONV_KERNEL_TAPS = 2,      /* 3x3 / 1x1 gather kernel with compile-time taps              */
+    ANR_CONV_KERNEL_BIGTAPS = 3,   /* 5x5 / 7x7 gather kernel, one channel per chunk              */
+    ANR_CONV_KERNEL_GATHER = 4,    /* any-geometry gather kernel                                  */
+    ANR_CONV_KERNEL_DIRECT = 5     /* one thread per output (extents beyond 32-bit offsets)       */
+};
+typedef struct {
+    int32_t kernel;                /* ANR_CONV_KERNEL_*                                           */
+    int32_t tile_m, tile_n;        /* 0 for ANR_CONV_KERNEL_DIRECT                                */
+    int32_t ksplit;                /* 1: no split                                                 */
+    int32_t wave_groups;           /* 1, 2 or 4                                                   */
+    int32_t work_groups;           /* launched by the main kernel                                 */
+    uint64_t workspace_bytes;      /* what this plan needs (<= anr_workspace_size)                */
+} anr_conv_route;
+anr_status anr_conv2d_route(const anr_conv_desc *desc, anr_conv_route *route);
+
 /* Static, NUL-terminated description of a status code. */
 const char *anr_status_string(anr_status status);
 

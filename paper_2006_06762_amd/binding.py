@@ -28,7 +28,7 @@ ANR_LAYOUT_NCHW = 0
 ANR_OP_GEMM, ANR_OP_CONV2D, ANR_OP_CONV_BN_RELU, ANR_OP_DWCONV, ANR_OP_TBG, ANR_OP_TBS, ANR_OP_NRM = range(7)
 
 EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
-           "anr_workspace_size", "anr_status_string", "anr_version", "anr_last_hip_error",
+           "anr_workspace_size", "anr_conv2d_route", "anr_status_string", "anr_version", "anr_last_hip_error",
            "anr_last_hip_error_string")
 
 
@@ -48,6 +48,16 @@ class ConvDesc(ctypes.Structure):
                 ("layout", ctypes.c_int32),
                 ("x_stride", ctypes.c_int64 * 4), ("y_stride", ctypes.c_int64 * 4),
                 ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class ConvRoute(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+                ("ksplit", ctypes.c_int32), ("wave_groups", ctypes.c_int32), ("work_groups", ctypes.c_int32),
+                ("workspace_bytes", ctypes.c_uint64)]
+
+
+ANR_CONV_KERNEL_PATCH, ANR_CONV_KERNEL_TAPS, ANR_CONV_KERNEL_BIGTAPS, ANR_CONV_KERNEL_GATHER, \
+    ANR_CONV_KERNEL_DIRECT = 1, 2, 3, 4, 5
 
 
 class NrmDesc(ctypes.Structure):
@@ -71,6 +81,7 @@ _lib.anr_tbg.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_s
 _lib.anr_tbs.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_nrm.argtypes = [ctypes.POINTER(NrmDesc), _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_workspace_size.argtypes = [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_size_t)]
+_lib.anr_conv2d_route.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ConvRoute)]
 for _name in ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
               "anr_workspace_size"):
     getattr(_lib, _name).restype = ctypes.c_int
@@ -144,6 +155,14 @@ def workspace_size(op: int, desc) -> int:
     _check(_lib.anr_workspace_size(op, ctypes.cast(ctypes.byref(desc), _vp), ctypes.byref(n)),
            "anr_workspace_size")
     return int(n.value)
+
+
+def conv2d_route(desc: ConvDesc) -> ConvRoute:
+    """Which kernel anr_conv2d would run for the descriptor (aligned pointers assumed), its tile,
+    split and workspace need; host-side planning only."""
+    r = ConvRoute()
+    _check(_lib.anr_conv2d_route(ctypes.byref(desc), ctypes.byref(r)), "anr_conv2d_route")
+    return r
 
 
 _workspaces = {}

@@ -313,6 +313,25 @@ anr_status anr_workspace_size(int op, const void* desc, size_t* bytes)
     return ANR_OK;
 }
 
+anr_status anr_conv2d_route(const anr_conv_desc* d, anr_conv_route* route)
+{
+    if (!route) return ANR_ERR_NULL;
+    ConvGeom cg;
+    const anr_status st = check_conv(d, false, &cg);
+    if (st != ANR_OK) return st;
+    const anr::ConvArgs a = make_conv_args(d, cg, nullptr, nullptr, nullptr);
+    anr::ConvRoute r{};
+    anr::describe_conv2d(a, &r);
+    route->kernel = r.kernel;
+    route->tile_m = r.tile_m;
+    route->tile_n = r.tile_n;
+    route->ksplit = r.ksplit;
+    route->wave_groups = r.wave_groups;
+    route->work_groups = r.work_groups;
+    route->workspace_bytes = r.workspace_bytes;
+    return ANR_OK;
+}
+
 const char* anr_status_string(anr_status status)
 {
     switch (status) {

@@ -251,6 +251,20 @@ size_t conv2d_gather_workspace_bytes(const ConvArgs& a)
     return need;
 }
 
+bool describe_conv2d_gather(const ConvArgs& a, ConvRoute* r)
+{
+    Plan g;
+    if (!(make_plan(a, &g) && choose_tile(a, &g))) return false;
+    r->kernel = g.taps >= 25 ? 3 : (g.taps ? 2 : 4);
+    r->tile_m = g.bm;
+    r->tile_n = g.bn;
+    r->ksplit = g.ksplit;
+    r->wave_groups = g.nwg;
+    r->work_groups = g.tiles_m * g.tiles_n * g.ksplit;
+    r->workspace_bytes = plan_workspace(g);
+    return true;
+}
+
 hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
     Plan g;

@@ -91,6 +91,29 @@ bool conv2d_igemm_takes(const ConvArgs& a)
     return (int64_t)g.tiles_m * g.tiles_n >= min_tuned_work_groups();
 }
 
+bool describe_conv2d_igemm(const ConvArgs& a, ConvRoute* r)
+{
+    Geom g;
+    size_t lds = 0;
+    const int best = select_variant(a, &g, &lds);
+    if (best < 0 || (int64_t)g.tiles_m * g.tiles_n < min_tuned_work_groups()) return false;
+    static const int kTileM[4] = {224, 224, 128, 64}, kTileN[4] = {64, 32, 64, 64};
+    r->kernel = 1;
+    r->tile_m = kTileM[best];
+    r->tile_n = kTileN[best];
+    r->ksplit = 1;
+    r->wave_groups = 1;
+    r->work_groups = g.tiles_m * g.tiles_n;
+    r->workspace_bytes = 0;
+    return true;
+}
+
+void describe_conv2d(const ConvArgs& a, ConvRoute* r)
+{
+    if (describe_conv2d_igemm(a, r) || describe_conv2d_gather(a, r)) return;
+    *r = ConvRoute{5, 0, 0, 1, 1, 0, 0};
+}
+
 hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
     *taken = false;

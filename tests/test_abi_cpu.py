@@ -203,3 +203,73 @@ def test_workspace_size():
         B.workspace_size(42, g)
     n = ctypes.c_size_t(0)
     assert B.raw().anr_workspace_size(0, None, ctypes.byref(n)) == B.ANR_ERR_NULL
+
+
+# ------------------------------------------------------------------ which kernel a convolution takes
+def route(x_shape, K, R, stride=1, pad=0, dil=1, groups=1):
+    d = B.conv_desc(x_shape, K, R, R, (stride, stride), (pad, pad), dil=(dil, dil), groups=groups)
+    return d, B.conv2d_route(d)
+
+
+def test_conv_route_benchmark_configs_take_the_patch_kernel():
+    # the three convolution launches of the benchmark step: tuned kernel, no split, no workspace
+    for shape, K, stride, tile in [((16, 64, 56, 56), 64, 1, (224, 64)), ((16, 128, 28, 28), 128, 1, (224, 32)),
+                                   ((16, 256, 28, 28), 512, 2, (224, 32))]:
+        d, r = route(shape, K, 3, stride, 1)
+        assert r.kernel == B.ANR_CONV_KERNEL_PATCH and (r.tile_m, r.tile_n) == tile
+        assert r.ksplit == 1 and r.workspace_bytes == 0 and r.work_groups == 224
+    # anr_workspace_size is the bound for any pointer alignment: the stride-2 layer would split its
+    # reduction in the general kernel if x or w were not 16-byte aligned
+    assert B.workspace_size(B.ANR_OP_CONV2D, B.conv_desc((16, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1))) == 0
+    assert B.workspace_size(B.ANR_OP_CONV2D, B.conv_desc((16, 256, 28, 28), 512, 3, 3, (2, 2), (1, 1))) > 0
+
+
+def test_conv_route_by_kernel_size_and_channels():
+    K = B
+    # few output tiles: the tuned kernel steps aside, the reduction is split through the workspace
+    d, r = route((1, 64, 56, 56), 64, 3, 1, 1)
+    assert r.kernel == K.ANR_CONV_KERNEL_TAPS and r.ksplit > 1 and r.workspace_bytes > 0
+    assert r.workspace_bytes <= K.workspace_size(K.ANR_OP_CONV2D, d)
+    # 14x14 and 7x7 maps (width not a multiple of 4), pointwise layers: compile-time taps, 64x64 tiles
+    for shape, Kout, R, pad in [((16, 256, 14, 14), 256, 3, 1), ((16, 512, 7, 7), 512, 3, 1), ((16, 64, 56, 56), 64, 1, 0),
+                                ((16, 1024, 14, 14), 256, 1, 0)]:
+        d, r = route(shape, Kout, R, 1, pad)
+        assert r.kernel == K.ANR_CONV_KERNEL_TAPS and (r.tile_m, r.tile_n) == (64, 64)
+        assert r.workspace_bytes <= K.workspace_size(K.ANR_OP_CONV2D, d)
+    # 7x7 stem and 5x5: one channel per chunk
+    assert route((16, 3, 224, 224), 64, 7, 2, 3)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
+    assert route((2, 32, 28, 28), 64, 5, 1, 2)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
+    # channel counts the tap kernels do not divide, other kernel sizes: any-geometry kernel
+    assert route((2, 6, 20, 20), 16, 3, 1, 1)[1].kernel == K.ANR_CONV_KERNEL_GATHER
+    assert route((2, 48, 20, 20), 16, 1)[1].kernel == K.ANR_CONV_KERNEL_GATHER
+    assert route((2, 8, 20, 20), 16, 4, 1, 1)[1].kernel == K.ANR_CONV_KERNEL_GATHER
+    # dilation and groups never take the patch kernel
+    assert route((16, 64, 56, 56), 64, 3, 1, 2, dil=2)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((16, 64, 56, 56), 64, 3, 1, 1, groups=4)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+
+
+def test_conv_route_wave_groups_and_split():
+    # about 200 tiles with a long chain and no split: two, then four groups of waves share it
+    r = route((4, 512, 7, 7), 2048, 1)[1]
+    assert (r.kernel, r.ksplit, r.wave_groups, r.work_groups) == (B.ANR_CONV_KERNEL_TAPS, 1, 2, 128)
+    r = route((16, 1024, 14, 14), 256, 1)[1]
+    assert (r.ksplit, r.wave_groups, r.work_groups) == (1, 4, 196)
+    # many tiles: one group, no split
+    r = route((16, 64, 56, 56), 256, 1)[1]
+    assert (r.ksplit, r.wave_groups) == (1, 1) and r.work_groups == 784 * 4
+    # the split never leaves a work-group without chunks and stays within the stated workspace
+    for shape, Kout, R, pad in [((1, 256, 14, 14), 256, 3, 1), ((1, 512, 7, 7), 512, 3, 1), ((4, 512, 7, 7), 512, 3, 1),
+                                ((1, 3, 224, 224), 64, 7, 3)]:
+        d, r = route(shape, Kout, R, 1 if R == 3 else 2, pad)
+        assert 1 <= r.ksplit <= 4608 and r.work_groups % r.ksplit == 0
+        assert r.workspace_bytes <= B.workspace_size(B.ANR_OP_CONV2D, d)
+        assert (r.workspace_bytes > 0) == (r.ksplit > 1)
+
+
+def test_conv_route_validation():
+    r = B.ConvRoute()
+    assert B.raw().anr_conv2d_route(None, ctypes.byref(r)) == B.ANR_ERR_NULL
+    d = B.conv_desc((1, 4, 8, 8), 8, 3, 3, (1, 1), (1, 1))
+    assert B.raw().anr_conv2d_route(ctypes.byref(d), None) == B.ANR_ERR_NULL
+    d.stride_h = 0
+    assert B.raw().anr_conv2d_route(ctypes.byref(d), ctypes.byref(r)) == B.ANR_ERR_INVALID_ARG
