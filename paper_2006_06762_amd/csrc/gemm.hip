@@ -411,18 +411,18 @@ hipError_t launch_variant(const GemmArgs& a, hipStream_t stream)
 }
 
 
-template <int BM, int BN, bool NT>
+template <int BM, int BN, bool NT, int NWG = 1>
 hipError_t launch_pipe(const GemmArgs& a, hipStream_t stream)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    const size_t lds_bytes = gpipe::Tiles<BM, BN, NT>::lds_bytes;
-    auto kern = gpipe::gemm_pipe_kernel<BM, BN, NT>;
+    const size_t lds_bytes = NWG * gpipe::Tiles<BM, BN, NT>::lds_bytes;
+    auto kern = gpipe::gemm_pipe_kernel<BM, BN, NT, NWG>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return launch_kernel(kern, dim3((unsigned)(tiles_m * tiles_n), 1, a.batch), dim3(256), lds_bytes, stream, a,
+    return launch_kernel(kern, dim3((unsigned)(tiles_m * tiles_n), 1, a.batch), dim3(256 * NWG), lds_bytes, stream, a,
                          tiles_m, tiles_n);
 }
 
@@ -437,6 +437,11 @@ hipError_t launch_pipe_any(const GemmArgs& a, hipStream_t stream)
     };
     if (tiles(128, 128) >= 512) return launch_pipe<128, 128, NT>(a, stream);
     if (tiles(128, 64) >= 512) return launch_pipe<128, 64, NT>(a, stream);
+    // at most one 64 x 64 tile per CU and a long reduction: groups of waves share the chunk chain
+    // (1024^3: 28.6 us with one group)
+    const int nchunks = (a.K + gpipe::KC - 1) / gpipe::KC;
+    if (tiles(64, 64) <= 256 && nchunks >= 32) return launch_pipe<64, 64, NT, 4>(a, stream);
+    if (tiles(64, 64) <= 256 && nchunks >= 8) return launch_pipe<64, 64, NT, 2>(a, stream);
     return launch_pipe<64, 64, NT>(a, stream);
 }
 

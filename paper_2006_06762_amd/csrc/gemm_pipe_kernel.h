@@ -37,8 +37,12 @@ struct Tiles {
     static constexpr size_t lds_bytes = sizeof(float) * 2 * (size_t)(A_SZ + B_SZ);
 };
 
-template <int BM, int BN, bool NT>
-__global__ __launch_bounds__(256) void gemm_pipe_kernel(const GemmArgs p, int tiles_m, int tiles_n)
+// NWG > 1 (64 x 64 tiles only): the work-group has NWG groups of four waves; group w takes every
+// NWG-th chunk through staging buffers of its own and the groups' accumulators meet in LDS at the
+// end.  For launches with at most one work-group per CU the chain of a work-group's chunks is what
+// takes the time (the matrix pipes idle between its barriers); sharing it among groups shortens it.
+template <int BM, int BN, bool NT, int NWG = 1>
+__global__ __launch_bounds__(256 * NWG) void gemm_pipe_kernel(const GemmArgs p, int tiles_m, int tiles_n)
 {
     using T = Tiles<BM, BN, NT>;
     constexpr int MB = BM / 64, NB = BN / 64;
@@ -46,11 +50,15 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const GemmArgs p, int ti
     constexpr int BU = BN / 32;                 // 16-byte units of B per thread and chunk
     constexpr int A_SZ = T::A_SZ, B_SZ = T::B_SZ, LDB = T::LDB;
 
-    extern __shared__ __attribute__((aligned(16))) float plds[];   // A[2][A_SZ], then B[2][B_SZ]
-    float* const lds_a = plds;
-    float* const lds_b = plds + 2 * A_SZ;
+    static_assert(NWG == 1 || (MB == 1 && NB == 1), "wave groups share 64 x 64 tiles only");
+    constexpr int REGION = 2 * (A_SZ + B_SZ);   // floats of staging per wave group
 
-    const int tid = threadIdx.x;
+    extern __shared__ __attribute__((aligned(16))) float plds[];   // per group: A[2][A_SZ], then B[2][B_SZ]
+    const int wgrp = NWG > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    float* const lds_a = plds + wgrp * REGION;
+    float* const lds_b = lds_a + 2 * A_SZ;
+
+    const int tid = (int)threadIdx.x & 255;     // thread inside its wave group
     const int lane = tid & 63, wave = tid >> 6;
     const int r32 = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
@@ -170,47 +178,67 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const GemmArgs p, int ti
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
 
-    load_chunk(0, S0{});
-    load_chunk(clampc(1), S1{});
+    // this group's chunks: wgrp, wgrp + NWG, ...; every group runs the same number of iterations
+    // (the barriers are the work-group's)
+    const int iters = (nchunks + NWG - 1) / NWG;
+    load_chunk(clampc(wgrp), S0{});
+    load_chunk(clampc(wgrp + NWG), S1{});
     store_chunk(0, S0{});
     __syncthreads();
 
-    // Iteration c: LDS buffer P holds chunk c, register set P is free, set P^1 holds chunk c+1.
+    // Iteration c: LDS buffer P holds chunk c, register set P is free, set P^1 holds the group's next chunk.
     auto iteration = [&](int c, auto par_c) {
         constexpr int P = decltype(par_c)::value;
-        load_chunk(clampc(c + 2), std::integral_constant<int, P>{});
+        load_chunk(clampc(c + 2 * NWG), std::integral_constant<int, P>{});
         // keep the loads ahead of the MFMAs (the scheduler would sink them to their first use)
         __builtin_amdgcn_sched_barrier(0);
         const float* a = lds_a + P * A_SZ + (wm * MB * 32 + r32) * WS + 2 * h;
         const float* b = NT ? lds_b + P * B_SZ + (wn * NB * 32 + r32) * WS + 2 * h
                             : lds_b + P * B_SZ + (2 * h) * LDB + wn * NB * 32 + r32;
+        if (NWG == 1 || c < nchunks) {          // a group may have one chunk fewer than the others
 #pragma unroll
-        for (int j = 0; j < KC / 4; ++j) {
-            f32x2 av[MB], bv[NB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WS + 4 * j);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                if (NT) {
-                    bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WS + 4 * j);
-                } else {
-                    bv[nb][0] = b[(4 * j) * LDB + nb * 32];
-                    bv[nb][1] = b[(4 * j + 1) * LDB + nb * 32];
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
+            for (int j = 0; j < KC / 4; ++j) {
+                f32x2 av[MB], bv[NB];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
+                    av[mb] = *reinterpret_cast<const f32x2*>(a + mb * 32 * WS + 4 * j);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (NT) {
+                        bv[nb] = *reinterpret_cast<const f32x2*>(b + nb * 32 * WS + 4 * j);
+                    } else {
+                        bv[nb][0] = b[(4 * j) * LDB + nb * 32];
+                        bv[nb][1] = b[(4 * j + 1) * LDB + nb * 32];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(av[mb][e], bv[nb][e], acc[mb][nb]);
+            }
         }
         store_chunk(P ^ 1, std::integral_constant<int, P ^ 1>{});
         __syncthreads();
     };
-    for (int c = 0; c < nchunks; c += 2) {
-        iteration(c, S0{});
-        if (c + 1 < nchunks) iteration(c + 1, S1{});
+    for (int i = 0; i < iters; i += 2) {
+        iteration(wgrp + i * NWG, S0{});
+        if (i + 1 < iters) iteration(wgrp + (i + 1) * NWG, S1{});
+    }
+    if (NWG > 1) {
+        // the last iteration ended with a barrier: every staging region is free.  Groups 1 .. NWG-1
+        // leave their accumulators in their own regions, group 0 adds them in group order.
+        if (wgrp > 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lds_a[(wave * 16 + r) * 64 + lane] = acc[0][0][r];
+        }
+        __syncthreads();
+        if (wgrp > 0) return;
+#pragma unroll
+        for (int o = 1; o < NWG; ++o)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][0][r] += plds[o * REGION + (wave * 16 + r) * 64 + lane];
     }
 
     // accumulator register r of lane (h, r32): row 8*(r/4) + 4*h + r%4, column r32 of the block

@@ -106,7 +106,10 @@ def test_gemm_batched_and_strided(anr):
 @pytest.mark.parametrize("M,N,K,batch", [(1024, 1024, 64, 8),      # 128 x 128 tiles of the pipelined kernel
                                           (1000, 1000, 100, 4),     # 128 x 64 tiles, ragged rows and columns
                                           (300, 200, 36, 3),        # 64 x 64 tiles, two chunks, ragged
-                                          (64, 64, 4, 1)])          # a single short chunk
+                                          (64, 64, 4, 1),           # a single short chunk
+                                          (640, 600, 388, 1),       # few tiles, 13 chunks: two groups of waves, one with a chunk fewer
+                                          (300, 500, 1000, 1),      # few tiles, 32 chunks with a K tail: four groups
+                                          (200, 260, 2048, 2)])     # four groups, batched
 @pytest.mark.parametrize("ints", [False, True])
 def test_gemm_pipelined_tiles(anr, M, N, K, batch, ints):
     A, B = I.gemm_inputs(I.GemmShape(M, N, K, batch), 110, ints=ints)
