@@ -13,6 +13,9 @@ def __getattr__(name):
     # Lazy: keep `import paper_2006_06762_amd.inputs` free of the HIP library.
     if name.startswith("__"):
         raise AttributeError(name)
+    if name == "build":
+        # the build script must import in a tree that has no built library yet
+        return importlib.import_module(__name__ + ".build")
     binding = importlib.import_module(__name__ + ".binding")
     if name == "binding":
         return binding
