@@ -913,3 +913,71 @@ def test_appendix_c_shapes_batch1(anr, golden_dir):
         assert_parity(out, oracle.tbg(q, k), what="TBG " + str(s))
         anr.tbs(dev(q), dev(k), out)
         assert_parity(out, oracle.tbs(q, k), what="TBS " + str(s))
+
+
+def test_appendix_c_gmm_batch16(anr, golden_dir):
+    """The GMM list at batch 16 (the paper's second batch size), full outputs against the oracle."""
+    for (n, m, k) in appendix_c(golden_dir)["GMM"]:
+        A, B = I.gemm_inputs(I.GemmShape(m, n, k, batch=16), 610)
+        C = torch.empty((16, m, n), device="cuda")
+        anr.gemm(dev(A), dev(B), C)
+        assert_parity(C, oracle.gemm(A, B), what="GMM x16 %s" % ((n, m, k),))
+
+
+def test_appendix_c_convolutions_batch16(anr, golden_dir):
+    """C2D, ConvLayer, GRP and DIL lists at batch 16, full outputs against the oracle."""
+    ops = appendix_c(golden_dir)
+    for (h, w_, ci, co, ks, st, pd) in ops["C2D"]:
+        s = I.ConvShape(16, ci, h, w_, co, ks, ks, (st, st), (pd, pd))
+        x, w = I.conv_inputs(s, 611)
+        y = torch.empty((16, co, s.OH, s.OW), device="cuda")
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+        assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), what="C2D x16 " + str(s))
+    for (h, w_, ci, co, ks, st, pd) in ops["ConvLayer"]:
+        s = I.ConvShape(16, ci, h, w_, co, ks, ks, (st, st), (pd, pd))
+        x, w = I.conv_inputs(s, 613)
+        gamma, beta, mean, var = I.bn_inputs(co, 614)
+        y = torch.empty((16, co, s.OH, s.OW), device="cuda")
+        anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y,
+                         s.stride, s.pad)
+        ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad)
+        assert_parity(y, ref, what="ConvLayer x16 " + str(s))
+    for op in ("GRP", "DIL"):
+        for fields in ops[op]:
+            s = I.appendix_shape(op, fields, 16)
+            if s is None:          # 3 input channels in 4 groups, as printed in the appendix
+                continue
+            x, w = I.conv_inputs(s, 616)
+            y = torch.empty((16, s.K, s.OH, s.OW), device="cuda")
+            anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, dil=s.dil, groups=s.groups)
+            ref = oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups)
+            assert_parity(y, ref, what=op + " x16 " + str(s))
+
+
+def test_appendix_c_dep_tbs_nrm_batch16(anr, golden_dir):
+    """DEP, TBS and NRM lists at batch 16 (the 4096 x 4096 NRM at batch 2: 16 of them are a gigabyte
+    of host input), full outputs against the oracle."""
+    ops = appendix_c(golden_dir)
+    for (h, w_, c, ks, st, pd) in ops["DEP"]:
+        s = I.ConvShape(16, c, h, w_, c, ks, ks, (st, st), (pd, pd))
+        x, w = I.dwconv_inputs(s, 612)
+        y = torch.empty((16, c, s.OH, s.OW), device="cuda")
+        anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+        assert_parity(y, oracle.dwconv(x, w, s.stride, s.pad), what="DEP x16 " + str(s))
+    for (S, H, D) in ops["TBS"]:
+        s = I.TbgShape(16, S, H, D)
+        q, k = I.tbg_inputs(s, 615)
+        q = (q * 0.35).astype(np.float32)
+        out = torch.empty((16, H, S, S), device="cuda")
+        anr.tbg(dev(q), dev(k), out)
+        assert_parity(out, oracle.tbg(q, k), what="TBG x16 " + str(s))
+        anr.tbs(dev(q), dev(k), out)
+        assert_parity(out, oracle.tbs(q, k), what="TBS x16 " + str(s))
+    for (n, m) in ops["NRM"]:
+        batch = 16 if n * m <= 1024 * 1024 else 2
+        x = I.uniform(np.random.Generator(np.random.PCG64(617)), (batch, n, m))
+        out = torch.empty((batch,), device="cuda")
+        anr.nrm(dev(x), out)
+        ref = oracle.nrm(x)
+        got = out.cpu().numpy().astype(np.float64)
+        assert float(np.max(np.abs(got - ref) / ref)) <= NRM_TOL, "NRM x%d %s" % (batch, (n, m))
