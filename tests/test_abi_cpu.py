@@ -266,6 +266,11 @@ def test_conv_route_wave_groups_and_split():
         assert (r.workspace_bytes > 0) == (r.ksplit > 1)
 
 
+def test_conv_route_beyond_32bit_offsets_is_the_direct_kernel():
+    r = route((1, 2, 16400, 16400), 1, 3, 1, 1)[1]
+    assert r.kernel == B.ANR_CONV_KERNEL_DIRECT and r.workspace_bytes == 0
+
+
 def test_conv_route_validation():
     r = B.ConvRoute()
     assert B.raw().anr_conv2d_route(None, ctypes.byref(r)) == B.ANR_ERR_NULL

@@ -981,3 +981,102 @@ def test_appendix_c_dep_tbs_nrm_batch16(anr, golden_dir):
         ref = oracle.nrm(x)
         got = out.cpu().numpy().astype(np.float64)
         assert float(np.max(np.abs(got - ref) / ref)) <= NRM_TOL, "NRM x%d %s" % (batch, (n, m))
+
+
+# ------------------------------------------------------------------ extents beyond 32-bit byte offsets
+def test_conv2d_extent_beyond_32bit_offsets(anr):
+    """An input of 2.15 GB (more than 2^29 floats): the kernels with 32-bit byte offsets step aside and
+    the call still has to index correctly.  Checked against the oracle on crops at the image's corners
+    and in its middle (the last rows are where a wrapped offset would show)."""
+    H = W = 16400
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    x = torch.rand((1, 2, H, W), generator=gen, device="cuda") * 2 - 1
+    w = (torch.rand((1, 2, 3, 3), generator=gen, device="cuda") * 2 - 1) * 0.25
+    y = torch.empty((1, 1, H, W), device="cuda")
+    anr.conv2d(x, w, y, (1, 1), (1, 1))
+    wh = w.cpu().numpy()
+    c = 40
+    # top-left and bottom-right corners: the crop's own padding is the image's on two sides
+    ref = oracle.conv2d(x[:, :, :c, :c].cpu().numpy(), wh, (1, 1), (1, 1))
+    assert_parity(y[:, :, :c - 1, :c - 1].contiguous(), ref[:, :, :c - 1, :c - 1], what="top-left crop")
+    ref = oracle.conv2d(x[:, :, H - c:, W - c:].cpu().numpy(), wh, (1, 1), (1, 1))
+    assert_parity(y[:, :, H - c + 1:, W - c + 1:].contiguous(), ref[:, :, 1:, 1:], what="bottom-right crop")
+    # interior crops: no padding, outputs of the crop's interior
+    for r0, c0 in [(H // 2, W // 2), (H - 3000, 17), (9000, W - 500)]:
+        ref = oracle.conv2d(x[:, :, r0:r0 + c, c0:c0 + c].cpu().numpy(), wh, (1, 1), (0, 0))
+        assert_parity(y[:, :, r0 + 1:r0 + c - 1, c0 + 1:c0 + c - 1].contiguous(), ref, what="crop at %d,%d" % (r0, c0))
+
+
+def test_gemm_extent_beyond_32bit_offsets(anr):
+    """A of 70000 x 8192 floats (2.3 GB): the pipelined kernel's 32-bit offsets do not reach, the
+    fallback must; rows at the start, in the middle and at the very end against the oracle."""
+    M, K, N = 70000, 8192, 8
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+    A = torch.rand((M, K), generator=gen, device="cuda") * 2 - 1
+    Bm = torch.rand((K, N), generator=gen, device="cuda") * 2 - 1
+    C = torch.empty((M, N), device="cuda")
+    anr.gemm(A, Bm, C)
+    Bh = Bm.cpu().numpy()
+    for r0 in (0, M // 2 - 7, M - 33):
+        rows = slice(r0, r0 + 33)
+        assert_parity(C[rows].contiguous(), oracle.gemm(A[rows].cpu().numpy(), Bh), what="rows from %d" % r0)
+
+
+def test_nrm_more_than_2_to_29_elements(anr):
+    """One 24000 x 24000 matrix (2.3 GB): slice offsets are 64-bit."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(99)
+    x = torch.rand((24000, 24000), generator=gen, device="cuda") * 2 - 1
+    out = torch.empty((1,), device="cuda")
+    anr.nrm(x, out)
+    ref = oracle.nrm(x.cpu().numpy())
+    assert abs(float(out[0]) - ref[0]) / ref[0] <= NRM_TOL
+
+
+def test_tbg_tbs_tensors_beyond_32bit_offsets(anr):
+    """q, k and the scores are 2.1 GB each (B 8, S 1024, H 64, D 1024; S 128 for the fused softmax):
+    the (b, h) base offsets are 64-bit; sampled heads against the oracle."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    B_, S, H, D = 8, 1024, 64, 1024
+    q = (torch.rand((B_, S, H, D), generator=gen, device="cuda") * 2 - 1) * 0.1
+    k = torch.rand((B_, S, H, D), generator=gen, device="cuda") * 2 - 1
+    out = torch.empty((B_, H, S, S), device="cuda")
+    anr.tbg(q, k, out)
+    for b, h in [(0, 0), (7, 63), (4, 31)]:
+        ref = oracle.tbg(q[b:b + 1, :, h:h + 1].cpu().numpy(), k[b:b + 1, :, h:h + 1].cpu().numpy())
+        assert_parity(out[b:b + 1, h:h + 1].contiguous(), ref, what="TBG head %d,%d" % (b, h))
+    del out
+    # the fused kernel on the same tensors, first 128 positions of every sequence (a strided view)
+    qv, kv = q[:, :128], k[:, :128]
+    outs = torch.empty((B_, H, 128, 128), device="cuda")
+    anr.tbs(qv, kv, outs)
+    for b, h in [(0, 0), (7, 63), (5, 17)]:
+        ref = oracle.tbs(qv[b:b + 1, :, h:h + 1].cpu().numpy(), kv[b:b + 1, :, h:h + 1].cpu().numpy())
+        assert_softmax_parity(outs[b:b + 1, h:h + 1].contiguous(), ref, what="TBS head %d,%d" % (b, h))
+
+
+def test_dwconv_tensor_beyond_32bit_offsets(anr):
+    """16 x 2048 planes of 128 x 128 (2.1 GB in, 2.1 GB out) through the row kernel, and of 14 x 14
+    with 700000 channels through the small-plane kernel: sampled planes against the oracle."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(55)
+    N, C, H = 16, 2048, 128
+    x = torch.rand((N, C, H, H), generator=gen, device="cuda") * 2 - 1
+    w = (torch.rand((C, 1, 3, 3), generator=gen, device="cuda") * 2 - 1) * 0.3
+    y = torch.empty((N, C, H, H), device="cuda")
+    anr.dwconv(x, w, y, (1, 1), (1, 1))
+    for n, c in [(0, 0), (15, 2047), (9, 1000)]:
+        ref = oracle.dwconv(x[n:n + 1, c:c + 1].cpu().numpy(), w[c:c + 1].cpu().numpy(), (1, 1), (1, 1))
+        assert_parity(y[n:n + 1, c:c + 1].contiguous(), ref, what="DEP plane %d,%d" % (n, c))
+    del x, y
+    N, C, H = 4, 700000, 14
+    x = torch.rand((N, C, H, H), generator=gen, device="cuda") * 2 - 1
+    w = (torch.rand((C, 1, 3, 3), generator=gen, device="cuda") * 2 - 1) * 0.3
+    y = torch.empty((N, C, 7, 7), device="cuda")
+    anr.dwconv(x, w, y, (2, 2), (1, 1))
+    for n, c in [(0, 0), (3, 699999), (2, 123457)]:
+        ref = oracle.dwconv(x[n:n + 1, c:c + 1].cpu().numpy(), w[c:c + 1].cpu().numpy(), (2, 2), (1, 1))
+        assert_parity(y[n:n + 1, c:c + 1].contiguous(), ref, what="DEP small plane %d,%d" % (n, c))
