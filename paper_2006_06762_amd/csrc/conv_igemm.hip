@@ -12,6 +12,7 @@ using namespace igemm;
 //                       WM WN  wM wN ks  R  S CPH   (tile = 32*WM*wM pixels x 32*WN*wN channels)
 using V224x64 = Variant<7, 1, 1, 2, 2, 3, 3, 4>;   // 4 waves: two 7x1-block tiles, 2-way k split
 using V224x32 = Variant<7, 1, 1, 1, 4, 3, 3, 4>;   // 4 waves share one 7x1-block tile along k
+using V224x32c16 = Variant<7, 1, 1, 1, 4, 3, 3, 8>; // the same tile with chunks of 16 channels (fixed-geometry instantiations only)
 using V128x64 = Variant<2, 2, 2, 1, 2, 3, 3, 4>;   // 4 waves, 2x2 blocks each, 2-way k split
 using V64x64 = Variant<2, 2, 1, 1, 4, 3, 3, 4>;    // 4 waves share one 2x2-block tile along k
 
@@ -127,7 +128,13 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
         case 0:
             if (try_fixed<V224x64, 3, 64, 384>(a, g, lds, stream, &err)) return err;    // 56x56 maps, stride 1
             return V224x64::launch(a, g, lds, stream);
-        case 1:
+        case 1: {
+            // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
+            Geom g8;
+            size_t lds8 = 0;
+            if (V224x32c16::plan(a, &g8, &lds8) && try_fixed<V224x32c16, 6, 36, 432>(a, g8, lds8, stream, &err))
+                return err;
+        }
             if (try_fixed<V224x32, 6, 36, 432>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 1
             if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
             return V224x32::launch(a, g, lds, stream);
