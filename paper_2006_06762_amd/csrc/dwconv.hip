@@ -1,4 +1,5 @@
 // Launch logic of the depthwise convolution (kernel in dwconv_kernel.h).
+#include <algorithm>
 #include "dwconv_kernel.h"
 
 namespace anr {
@@ -40,14 +41,15 @@ hipError_t launch_small_planes(const ConvArgs& a, hipStream_t stream, bool* take
     const int64_t hw = (int64_t)a.H * a.W, ohw = (int64_t)a.OH * a.OW;
     const bool dense = a.xs[2] == a.W && a.xs[1] == hw && a.xs[0] == a.C * hw && a.ys[2] == a.OW && a.ys[1] == ohw &&
                        a.ys[0] == a.C * ohw && is_aligned16(a.x) && is_aligned16(a.y);
-    // at most about eight outputs per thread, ranges that start 16-byte aligned, and at least three
-    // work-groups per CU where the tensor has that many planes
+    // at most about eight outputs per thread, ranges that start 16-byte aligned (G a multiple of
+    // `unit`), and at least three work-groups per CU where the tensor has that many planes
     const int64_t planes = (int64_t)a.N * a.C;
-    int G = (int)(2048 / ohw) & ~3;
-    if (G > 256) G = 256;
-    if (!dense || G == 0 || a.C >= (1 << 30)) return hipSuccess;
-    const int64_t spread = (planes / 768) & ~(int64_t)3;
-    if (spread < G) G = spread < 4 ? 4 : (int)spread;
+    if (!dense || ohw > 2048 || a.C >= (1 << 30)) return hipSuccess;
+    const int unit = ((hw | ohw) % 4 == 0) ? 1 : ((hw | ohw) % 2 == 0) ? 2 : 4;
+    const int g_max = (int)std::min<int64_t>(256, 2048 / ohw) / unit * unit;
+    if (g_max == 0) return hipSuccess;
+    int G = (int)std::min<int64_t>(g_max, planes / 768 / unit * unit);
+    if (G < unit) G = unit;
     const int64_t rs = (int64_t)a.R * a.S;
     const int64_t lds_floats = ((G * hw + 3) & ~(int64_t)3) + ((G * ohw + 3) & ~(int64_t)3) + G * rs;
     if (lds_floats * 4 > 48 * 1024 || planes >= ((int64_t)1 << 31) || (planes + G - 1) / G >= ((int64_t)1 << 31))
@@ -65,6 +67,8 @@ hipError_t launch_small_planes(const ConvArgs& a, hipStream_t stream, bool* take
     const dim3 grid((unsigned)((planes + G - 1) / G));
     if (a.R == 3 && a.S == 3)
         return launch_kernel(dw::dwconv_small_planes_kernel<3, 3>, grid, dim3(256), (size_t)lds_floats * 4, stream, a, g);
+    if (a.R == 5 && a.S == 5)
+        return launch_kernel(dw::dwconv_small_planes_kernel<5, 5>, grid, dim3(256), (size_t)lds_floats * 4, stream, a, g);
     return launch_kernel(dw::dwconv_small_planes_kernel<0, 0>, grid, dim3(256), (size_t)lds_floats * 4, stream, a, g);
 }
 

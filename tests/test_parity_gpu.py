@@ -476,10 +476,19 @@ def test_dwconv_small(anr, shape, ints):
 
 def test_dwconv_small_planes_many_planes(anr):
     """Small maps with enough planes that a work-group stages several of them through LDS, the last
-    work-group with fewer (plane count not a multiple of the group); 3x3 and a 5x2 kernel."""
+    work-group with fewer (plane count not a multiple of the group); 3x3, 5x5 and a 5x2 kernel.
+    Then plane sizes that allow groups of one plane (H*W and OH*OW multiples of 4) and of two
+    (both even), with few planes, so that the smallest group is the one taken."""
     for s in [I.ConvShape(2, 3101, 7, 7, 3101, 3, 3, (1, 1), (1, 1)),
               I.ConvShape(1, 6150, 14, 14, 6150, 3, 3, (2, 2), (1, 1)),
-              I.ConvShape(3, 2051, 6, 5, 2051, 5, 2, (1, 2), (2, 0))]:
+              I.ConvShape(3, 2051, 6, 5, 2051, 5, 2, (1, 2), (2, 0)),
+              I.ConvShape(2, 1543, 14, 14, 1543, 5, 5, (1, 1), (2, 2)),
+              I.ConvShape(1, 3079, 14, 14, 3079, 5, 5, (2, 2), (2, 2)),
+              I.ConvShape(1, 37, 28, 28, 37, 3, 3, (2, 2), (1, 1)),
+              I.ConvShape(3, 11, 30, 30, 11, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(1, 45, 10, 9, 45, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(2, 19, 22, 18, 19, 5, 5, (1, 1), (2, 2)),
+              I.ConvShape(1, 5, 44, 44, 5, 5, 5, (1, 1), (0, 0))]:
         x, w = I.dwconv_inputs(s, 470, ints=True)
         buf, y = guarded((s.N, s.C, s.OH, s.OW))
         anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
