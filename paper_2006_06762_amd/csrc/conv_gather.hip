@@ -37,6 +37,22 @@ bool make_plan(const ConvArgs& a, Plan* g, bool allow_taps = true)
     g->RS = a.R * a.S;
     g->Cg = a.C / a.groups;
     g->Kg = a.K / a.groups;
+    g->groups = a.groups;
+    g->pack_cg = g->pack_kg = 0;
+    g->d_pack_kg = make_fastdiv(1);
+    // 1 x 1 kernels of small groups: 64 / Kg groups share a column tile (conv_taps_kernel, PACK)
+    if (allow_taps && is_aligned16(a.w) && a.R == 1 && a.S == 1 && a.groups > 1 && g->Kg < 64 && 64 % g->Kg == 0 &&
+        g->Cg % 4 == 0 && (g->Kg <= 16 || g->Cg % 32 != 0)) {
+        const int pack = 64 / g->Kg;
+        if (a.groups % pack == 0 && (pack * g->Cg) % 32 == 0) {
+            g->pack_cg = g->Cg;
+            g->pack_kg = g->Kg;
+            g->d_pack_kg = make_fastdiv(g->Kg);
+            g->groups = a.groups / pack;
+            g->Cg *= pack;
+            g->Kg = 64;
+        }
+    }
     g->Ktot = g->Cg * g->RS;
     g->d_kg = make_fastdiv(g->Kg);
     // 3 x 3 and 1 x 1 kernels whose channels fill whole chunks take the form with compile-time taps
@@ -71,7 +87,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     g->bn = bn;
     g->tiles_m = (g->Mtot + bm - 1) / bm;
     g->tiles_ng = (g->Kg + bn - 1) / bn;
-    g->tiles_n = a.groups * g->tiles_ng;
+    g->tiles_n = g->groups * g->tiles_ng;
     g->d_tiles_ng = make_fastdiv(g->tiles_ng);
     if (ks > g->nchunks) ks = g->nchunks;
     g->chunks_per_split = (g->nchunks + ks - 1) / ks;
@@ -85,7 +101,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     // chunks 27.7 -> 24.3 us; with more work-groups per CU or short chains the larger work-groups
     // only cost occupancy)
     g->nwg = 1;
-    if ((g->taps == 9 || g->taps == 1) && (int64_t)g->tiles_m * g->tiles_n * g->ksplit <= kCUs) {
+    if ((g->taps == 9 || g->taps == 1) && g->pack_cg == 0 && (int64_t)g->tiles_m * g->tiles_n * g->ksplit <= kCUs) {
         if (g->chunks_per_split >= 32) g->nwg = 4;
         else if (g->chunks_per_split >= 8) g->nwg = 2;
     }
@@ -100,7 +116,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
 // measurements on the shape lists of Appendix C.
 double estimate_us(const Plan& g, const ConvArgs& a, const Tile& t, int ks)
 {
-    const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * a.groups * ((g.Kg + t.bn - 1) / t.bn);
+    const int64_t tiles = (int64_t)((g.Mtot + t.bm - 1) / t.bm) * g.groups * ((g.Kg + t.bn - 1) / t.bn);
     const int cps = (g.nchunks + ks - 1) / ks;
     const int ks_eff = (g.nchunks + cps - 1) / cps;
     const int64_t wgs = tiles * ks_eff;
@@ -125,7 +141,7 @@ double estimate_taps_us(const Plan& g, const ConvArgs& a, int ks)
 {
     constexpr double kPrologueUs = 0.9, kLoneUs = 0.78, kChunkUs = 0.65;   // per chunk of 36
     constexpr double kMainUs = 2.6, kReduceUs = 4.5, kWsRate = 4.85e6;     // launches; workspace bytes per us
-    const int64_t tiles = (int64_t)((g.Mtot + 63) / 64) * a.groups * ((g.Kg + 63) / 64);
+    const int64_t tiles = (int64_t)((g.Mtot + 63) / 64) * g.groups * ((g.Kg + 63) / 64);
     const int cps = (g.nchunks + ks - 1) / ks;
     const int ks_eff = (g.nchunks + cps - 1) / cps;
     const int64_t wgs = tiles * ks_eff;
@@ -143,7 +159,7 @@ bool choose_tile(const ConvArgs& a, Plan* g)
     bool have = false;
     int bm = 0, bn = 0, bks = 1;
     if (g->taps) {
-        const int64_t tiles = (int64_t)((g->Mtot + 63) / 64) * a.groups * ((g->Kg + 63) / 64);
+        const int64_t tiles = (int64_t)((g->Mtot + 63) / 64) * g->groups * ((g->Kg + 63) / 64);
         if (tiles >= ((int64_t)1 << 24)) return false;
         const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;
         int last_cps = 0;
@@ -163,7 +179,7 @@ bool choose_tile(const ConvArgs& a, Plan* g)
         return true;
     }
     for (const Tile& t : kTiles) {
-        const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * a.groups * ((g->Kg + t.bn - 1) / t.bn);
+        const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * g->groups * ((g->Kg + t.bn - 1) / t.bn);
         if (tiles >= ((int64_t)1 << 24)) continue;
         const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;      // enough tiles: no split
         int last_cps = 0;
@@ -206,11 +222,11 @@ hipError_t launch_tile_as(const ConvArgs& a, const Plan& g, hipStream_t stream)
     return launch_kernel(kern, dim3(grid), dim3(256), lds_bytes, stream, a, g);
 }
 
-template <int BM, int BN, int R_, int S_, int NWG>
+template <int BM, int BN, int R_, int S_, int NWG, bool PACK = false>
 hipError_t launch_tile_taps(const ConvArgs& a, const Plan& g, hipStream_t stream)
 {
     const size_t lds_bytes = sizeof(float) * NWG * 2 * (size_t)(BM + BN) * (g.kc + 2);
-    auto kern = conv_taps_kernel<BM, BN, R_, S_, NWG>;
+    auto kern = conv_taps_kernel<BM, BN, R_, S_, NWG, PACK>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -286,7 +302,9 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
             err = g.taps == 49 ? launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g)
                                : launch_kernel(conv_bigtaps_kernel<5, 5>, dim3(grid), dim3(256), lds_bytes, stream, a, g);
         } else {
-            err = g.taps == 9 ? launch_taps_groups<3, 3>(a, g, stream) : launch_taps_groups<1, 1>(a, g, stream);
+            err = g.taps == 9     ? launch_taps_groups<3, 3>(a, g, stream)
+                  : g.pack_cg > 0 ? launch_tile_taps<64, 64, 1, 1, 1, true>(a, g, stream)
+                                  : launch_taps_groups<1, 1>(a, g, stream);
         }
     } else if (g.bm == 128 && g.bn == 128) err = launch_tile<128, 128>(a, g, stream);
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);

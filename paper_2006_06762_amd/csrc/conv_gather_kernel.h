@@ -43,7 +43,10 @@ constexpr int kMaxExtent = 16000;               // image height/width and kernel
 struct Plan {
     int Mtot, ohow, RS;
     int Ktot;                    // reduction length: (C / groups) * R * S
-    int Cg, Kg;                  // input / output channels per group
+    int Cg, Kg;                  // input / output channels per group (per pack of groups when pack_cg > 0)
+    int groups;                  // groups, or packs of groups
+    int pack_cg, pack_kg;        // conv_taps_kernel with packed groups: channels of ONE group; else 0
+    FastDiv d_pack_kg;
     int tiles_ng;                // column tiles per group (a tile never straddles two groups)
     int tiles_m, tiles_n, ksplit, nchunks, chunks_per_split;
     int Mpad, Kpad;              // tile-padded extents of the workspace
@@ -379,9 +382,18 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
 // at the end.  For launches with one work-group per CU (batch 1: the chain of a work-group's
 // chunks is what takes the time, and the matrix pipes idle between its barriers) this shortens the
 // chain NWG-fold without more partial tiles in the workspace.
-template <int BM, int BN, int R_, int S_, int NWG>
+//
+// PACK (1 x 1 kernels of grouped convolutions whose groups have fewer than 64 output channels): a
+// column tile takes 64 / Kg consecutive groups at once as ONE group with a block-diagonal weight
+// matrix.  The pixel gather, the tile and the stores are those of a convolution with that many
+// fewer, larger groups; only the weight units differ: a unit of row co is real inside the channel
+// range of co's own group and zero (an out-of-range load) elsewhere.  The extra products are
+// zeros on matrix pipes that idle anyway; what is saved is one work-group, one pixel gather and
+// three quarters of a column tile per group (56 x 56, 64 -> 64, 4 groups, batch 16: 22 -> 12 us).
+template <int BM, int BN, int R_, int S_, int NWG, bool PACK = false>
 __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, const Plan g)
 {
+    static_assert(!PACK || (R_ == 1 && S_ == 1 && NWG == 1), "packed groups: 1 x 1 kernels, one wave group");
     constexpr int T = R_ * S_;
     constexpr int CPC = T == 1 ? 32 : 4;            // channels per chunk
     constexpr int KCT = CPC * T;                    // reduction elements per chunk
@@ -442,14 +454,23 @@ __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, 
     // ---- this thread's weight units: unit u is 16 bytes of row u / UPR; slots past the tile's
     //      units duplicate an earlier one (same data to the same place), columns past the group
     //      repeat its last (never stored)
+    //      PACK: a weight row holds the pack_cg channels of its own group; wk is the unit's first
+    //      channel of the FIRST chunk relative to that group's first channel (negative before it)
     uint32_t wvoff[BU], wlds[BU];
+    int wk[BU];
 #pragma unroll
     for (int j = 0; j < BU; ++j) {
         const int u = (tid + 256 * j) % BUNITS;
         const int row = u / UPR, q = u - row * UPR;
         int co = cl0 + row;
-        co = cog + (co < g.Kg ? co : g.Kg - 1);
-        wvoff[j] = 4u * (uint32_t)(co * g.Ktot + 4 * q);
+        co = co < g.Kg ? co : g.Kg - 1;
+        if (PACK) {
+            wk[j] = 4 * q - g.d_pack_kg.div(co) * g.pack_cg;
+            wvoff[j] = 4u * (uint32_t)((cog + co) * g.pack_cg + wk[j]);     // never negative: co >= its group index
+        } else {
+            wk[j] = 0;
+            wvoff[j] = 4u * (uint32_t)((cog + co) * g.Ktot + 4 * q);
+        }
         wlds[j] = (uint32_t)(row * WST + 4 * q);
     }
     const __amdgpu_buffer_rsrc_t xrsrc =
@@ -471,9 +492,13 @@ __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, 
                 ra[set][cc * T + t] = __builtin_bit_cast(
                     float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)voff[t], 4 * (c0 + cc) * xs1, 0));
 #pragma unroll
-        for (int j = 0; j < BU; ++j)
+        for (int j = 0; j < BU; ++j) {
+            // PACK: the unit is inside its group's block of this chunk or it is zero
+            const uint32_t off =
+                (!PACK || (unsigned)(chunk * KCT + wk[j]) < (unsigned)g.pack_cg) ? wvoff[j] : kOutOfRange;
             rb[set][j] = __builtin_bit_cast(
-                f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)wvoff[j], 4 * chunk * KCT, 0));
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 4 * chunk * KCT, 0));
+        }
     };
     auto store_chunk = [&](int buf, auto set_c) {
         constexpr int set = decltype(set_c)::value;

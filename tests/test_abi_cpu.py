@@ -266,6 +266,19 @@ def test_conv_route_wave_groups_and_split():
         assert (r.workspace_bytes > 0) == (r.ksplit > 1)
 
 
+def test_conv_route_packs_small_groups_of_pointwise_layers():
+    # 56x56, 64 -> 64, 1x1, 4 groups of 16 channels: the four groups share one 64-wide column tile
+    # (784 work-groups, as for the ungrouped layer) instead of taking a quarter-filled tile each
+    r = route((16, 64, 56, 56), 64, 1, groups=4)[1]
+    assert (r.kernel, r.tile_n, r.ksplit, r.wave_groups, r.work_groups) == (B.ANR_CONV_KERNEL_TAPS, 64, 1, 1, 784)
+    # 32 groups of 4 output channels: two packs of 16 groups
+    assert route((16, 256, 28, 28), 128, 1, groups=32)[1].work_groups == 196 * 2
+    # groups of 64 output channels and more are not packed; neither are 12 groups (not a multiple of 4)
+    assert route((16, 256, 28, 28), 256, 1, groups=4)[1].work_groups == 196 * 4
+    r = route((1, 48, 5, 5), 48, 1, groups=12)[1]
+    assert r.kernel == B.ANR_CONV_KERNEL_GATHER and r.work_groups % 12 == 0
+
+
 def test_conv_route_beyond_32bit_offsets_is_the_direct_kernel():
     r = route((1, 2, 16400, 16400), 1, 3, 1, 1)[1]
     assert r.kernel == B.ANR_CONV_KERNEL_DIRECT and r.workspace_bytes == 0

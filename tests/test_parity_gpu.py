@@ -296,6 +296,43 @@ def test_conv2d_grouped_dilated(anr, shape, ints):
     assert_parity(y, ref, exact=ints, what=str(shape))
 
 
+# 1 x 1 kernels of small groups: 64 / Kg groups share a column tile with a block-diagonal weight tile.
+# Packs of 8, 16, 4 and 2 groups, several packs, several chunks per pack, stride and padding (a 1 x 1
+# tap that leaves the image), a pixel count that is not a multiple of the tile, and a case whose few
+# tiles make the planner split the reduction.
+PACKED_GROUP_SHAPES = [
+    I.ConvShape(2, 64, 9, 11, 64, 1, 1, (1, 1), (0, 0), (1, 1), 8),
+    I.ConvShape(1, 128, 13, 7, 64, 1, 1, (1, 1), (0, 0), (1, 1), 16),
+    I.ConvShape(3, 64, 10, 10, 64, 1, 1, (2, 2), (1, 1), (1, 1), 4),
+    I.ConvShape(1, 96, 8, 9, 192, 1, 1, (1, 1), (0, 0), (1, 1), 6),
+    I.ConvShape(2, 256, 6, 6, 128, 1, 1, (1, 1), (0, 0), (1, 1), 32),
+    I.ConvShape(1, 512, 7, 7, 128, 1, 1, (1, 1), (0, 0), (1, 1), 8),
+    I.ConvShape(1, 48, 5, 5, 48, 1, 1, (1, 1), (0, 0), (1, 1), 12),      # 3 packs of 4 groups would need 48 % 32 == 0: general kernel
+]
+
+
+@pytest.mark.parametrize("shape", PACKED_GROUP_SHAPES, ids=str)
+@pytest.mark.parametrize("ints", [False, True])
+def test_conv2d_packed_groups(anr, shape, ints):
+    x, w = I.conv_inputs(shape, 230, ints=ints)
+    buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
+    anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad, dil=shape.dil, groups=shape.groups)
+    check_guard(buf)
+    ref = oracle.conv2d_general(x, w, shape.stride, shape.pad, shape.dil, shape.groups)
+    assert_parity(y, ref, exact=ints, what=str(shape))
+
+
+def test_conv_bn_relu_packed_groups(anr):
+    s = I.ConvShape(2, 64, 12, 12, 64, 1, 1, (1, 1), (0, 0), (1, 1), 4)
+    x, w = I.conv_inputs(s, 231)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 232)
+    y = torch.empty((s.N, s.K, s.OH, s.OW), device="cuda")
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad,
+                     dil=s.dil, groups=s.groups)
+    ref = oracle.conv_bn_relu_general(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad, s.dil, s.groups)
+    assert_parity(y, ref, what="packed-group ConvLayer")
+
+
 def test_conv_bn_relu_grouped_dilated(anr):
     s = I.ConvShape(2, 16, 10, 10, 24, 3, 3, (1, 1), (2, 2), (2, 2), 4)
     x, w = I.conv_inputs(s, 221)
