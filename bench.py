@@ -13,10 +13,13 @@ all inputs resident in HBM.  Prints ONE JSON line:
              replayed HIP graph of 48 launches), warm (same buffers) and cold (24 rotating
              buffer sets), TFLOP/s against the 157.3 TFLOP/s fp32 MFMA peak and GB/s
              against 8 TB/s; us_cold_eager is the same launch issued from Python;
+  overlapped the same step with its independent operators on three streams of one HIP graph
+             (forked and joined every step): ms_per_step and TFLOP/s beside `value`, which
+             stays the one-stream figure; --no-overlap skips it;
   roofline   the dominant kernel (the implicit-GEMM convolution on its largest launch);
   cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample.
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--eager]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--eager] [--no-overlap]
 """
 import argparse
 import json
@@ -154,6 +157,47 @@ def time_graph(torch, fn, launches, replays=10):
     return start.elapsed_time(end) * 1000.0 / (launches * replays)
 
 
+# Independent operators of a step on separate streams: the stride-2 convolution alone, the two
+# stride-1 convolutions one after the other, the three short kernels one after the other.  The
+# convolution kernels hold one work-group per CU on 224 of the 256 CUs and leave a SIMD idle at
+# every barrier; kernels of other streams run in those gaps.
+OVERLAP_PLAN = (("C2D_S2",), ("C2D", "ConvLayer"), ("GMM", "TBG", "DEP"))
+
+
+def overlapped_steps(torch, sets, group, steps):
+    """Milliseconds per step when the step's six launches are issued on three streams (forked from
+    and joined to the main stream in every step) inside one HIP graph of `group` steps."""
+    main = torch.cuda.Stream()
+    side = [torch.cuda.Stream() for _ in OVERLAP_PLAN[1:]]     # default priority, like every stream here
+    main.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(main):
+        with torch.cuda.graph(graph, stream=main):
+            for i in range(group):
+                s = sets[i % 4]
+                for st in side:
+                    st.wait_stream(main)
+                for ops, st in zip(OVERLAP_PLAN[1:], side):
+                    with torch.cuda.stream(st):
+                        for n in ops:
+                            s.run(n)
+                for n in OVERLAP_PLAN[0]:
+                    s.run(n)
+                for st in side:
+                    main.wait_stream(st)
+        graph.replay()                           # untimed: uploads the graph
+        main.synchronize()
+        torch.cuda.synchronize()
+        replays = max(1, steps // group)
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        main.synchronize()
+        wall = time.perf_counter() - t0
+    torch.cuda.current_stream().wait_stream(main)
+    return wall * 1000.0 / (replays * group)
+
+
 def shape_list(anr, I, torch):
     """Launch times of every Appendix C shape at batch 1 and 16 (operator and subgraph benchmarks,
     Sec. 7.1 and 7.2).  Timing only: values are uniform random numbers drawn on the device."""
@@ -285,6 +329,9 @@ def main():
                     help="skip the oracle timing and parity check (profiling runs)")
     ap.add_argument("--eager", action="store_true",
                     help="issue every timed step from Python instead of replaying a HIP graph of steps")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="skip the extra timing of the step with its operators on three streams (profiling runs: "
+                         "keeps every kernel's launches free of other kernels)")
     ap.add_argument("--only", default=None, help="profiling aid: launch only this operator in the step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
@@ -447,6 +494,25 @@ def main():
         "peaks": {"mfma_f32_tflops": PEAK_MFMA_F32_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
         "per_op": per_op,
     }
+
+    if group and args.only is None and not args.no_overlap:
+        # the same step with independent operators overlapped; outputs must be bit-identical to the
+        # one-stream step's (same kernels on the same inputs)
+        seq = {}
+        sets[0].step()
+        torch.cuda.synchronize()
+        for n in names:
+            seq[n] = sets[0].output(n).clone()
+            sets[0].output(n).zero_()
+        ms_overlap = overlapped_steps(torch, sets, group, args.steps)
+        torch.cuda.synchronize()
+        out["overlapped"] = {
+            "ms_per_step": ms_overlap, "value": step_flops / (ms_overlap * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "streams": [list(ops) for ops in OVERLAP_PLAN], "steps_per_graph_replay": group,
+            "outputs_identical": all(bool(torch.equal(seq[n], sets[0].output(n))) for n in names),
+            "note": "same six launches per step, independent operators on three streams of one HIP graph, "
+                    "joined every step; `value` above is the one-stream step",
+        }
 
     if not args.no_cpu_baseline and args.only is None:
         refs, base = cpu_baseline(I, host, table)

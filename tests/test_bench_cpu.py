@@ -35,6 +35,14 @@ def test_workload_table_matches_the_shapes():
     assert abs(total / 1e9 - 15.53) < 0.01
 
 
+def test_overlap_plan_launches_every_operator_of_the_step_once():
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2006_06762_amd import inputs as I
+    flat = [n for ops in bench.OVERLAP_PLAN for n in ops]
+    assert sorted(flat) == sorted(I.CONFIG_NAMES)
+
+
 def test_trace_summary_reads_a_kernel_table(tmp_path):
     sys.path.insert(0, ROOT)
     import bench

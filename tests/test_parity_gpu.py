@@ -1126,3 +1126,30 @@ def test_dwconv_tensor_beyond_32bit_offsets(anr):
     for n, c in [(0, 0), (3, 699999), (2, 123457)]:
         ref = oracle.dwconv(x[n:n + 1, c:c + 1].cpu().numpy(), w[c:c + 1].cpu().numpy(), (2, 2), (1, 1))
         assert_parity(y[n:n + 1, c:c + 1].contiguous(), ref, what="DEP small plane %d,%d" % (n, c))
+
+
+# ------------------------------------------------------------------ the step on several streams
+def test_step_on_three_streams_in_one_graph_matches_the_one_stream_step(anr):
+    """bench.py's overlapped step: the six launches forked onto three streams inside one HIP graph.
+    Replayed three times with eager work and synchronisation in between; after every replay all six
+    outputs must equal the one-stream step's bit for bit (same kernels, same inputs)."""
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    host = {name: I.config_inputs(name) for name in I.CONFIG_NAMES}
+    sets = [bench.OpSet(anr, I, torch, host) for _ in range(4)]
+    sets[0].step()
+    torch.cuda.synchronize()
+    want = {n: sets[0].output(n).clone() for n in I.CONFIG_NAMES}
+    for rep in range(3):
+        for s in sets:
+            for n in I.CONFIG_NAMES:
+                s.output(n).fill_(CANARY)            # eager work between the replays
+        torch.cuda.synchronize()
+        ms = bench.overlapped_steps(torch, sets, 4, 4)
+        torch.cuda.synchronize()
+        assert ms > 0
+        for s in sets:
+            for n in I.CONFIG_NAMES:
+                assert torch.equal(s.output(n), want[n]), "replay %d: %s differs" % (rep, n)
