@@ -105,9 +105,10 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
         if (g->chunks_per_split >= 32) g->nwg = 4;
         else if (g->chunks_per_split >= 8) g->nwg = 2;
     }
-    // whole tiles stored in runs of 64 pixels per channel (1 x 1 layers, 56 x 56 and 28 x 28 maps at
-    // batch 16: 3-4 % faster than one 16-byte piece per lane and channel)
-    g->tstore = (g->taps == 9 || g->taps == 1) && g->nwg == 1 && g->ksplit == 1 && g->vec_store;
+    // tiles stored in runs of 64 pixels per channel (1 x 1 layers, 56 x 56 and 28 x 28 maps at batch 16:
+    // 3-4 % faster than one 16-byte piece per lane and channel; partial tiles of a split reduction,
+    // whose workspace is padded and aligned: 1-2 %)
+    g->tstore = (g->taps == 9 || g->taps == 1) && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
     g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
     g->d_rblocks = make_fastdiv(g->rblocks);
 }

@@ -602,7 +602,10 @@ __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, 
         for (int k = 0; k < 4; ++k) {
             const int ch = (tid >> 4) + 16 * k, quad = tid & 15;
             const f32x4 v = *reinterpret_cast<const f32x4*>(t + ch * TS + 4 * quad);
-            if (cl0 + ch < g.Kg) {
+            if (g.ksplit > 1) {
+                // partial tile: the workspace is padded to whole tiles
+                stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * 64 + ch) * g.Mpad + m0 + 4 * quad, v);
+            } else if (cl0 + ch < g.Kg) {
                 float scale = 1.f, shift = 0.f;
                 if (p.gamma) bn_constants(p, cog + cl0 + ch, &scale, &shift);
                 store_quad(p, g, m0 + 4 * quad, cog + cl0 + ch, v, scale, shift);
