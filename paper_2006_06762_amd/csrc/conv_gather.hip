@@ -1,5 +1,6 @@
 // Tile and split-K selection and launch of the general implicit-GEMM convolution (kernels
 // and their description in conv_gather_kernel.h).
+#include <algorithm>
 #include "conv_gather_kernel.h"
 
 namespace anr {
@@ -106,9 +107,9 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
         else if (g->chunks_per_split >= 8) g->nwg = 2;
     }
     // tiles stored in runs of 64 pixels per channel (1 x 1 layers, 56 x 56 and 28 x 28 maps at batch 16:
-    // 3-4 % faster than one 16-byte piece per lane and channel; partial tiles of a split reduction,
-    // whose workspace is padded and aligned: 1-2 %)
-    g->tstore = (g->taps == 9 || g->taps == 1) && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
+    // 3-4 % faster than one 16-byte piece per lane and channel; the 7 x 7 stem at batch 16, which writes
+    // 51 MB: 7 %; partial tiles of a split reduction, whose workspace is padded and aligned: 1-2 %)
+    g->tstore = g->taps != 0 && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
     g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
     g->d_rblocks = make_fastdiv(g->rblocks);
 }
@@ -301,7 +302,8 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     if (g.taps) {
         if (g.bm != 64 || g.bn != 64) return hipErrorInvalidValue;
         if (g.taps >= 25) {
-            const size_t lds_bytes = sizeof(float) * (size_t)(64 + 64) * (g.kc + 2);
+            // staging tiles, or the transposed output tile of the epilogue if that is larger
+            const size_t lds_bytes = sizeof(float) * std::max<size_t>((size_t)(64 + 64) * (g.kc + 2), kRunTileFloats);
             const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
             err = g.taps == 49 ? launch_kernel(conv_bigtaps_kernel<7, 7>, dim3(grid), dim3(256), lds_bytes, stream, a, g)
                                : launch_kernel(conv_bigtaps_kernel<5, 5>, dim3(grid), dim3(256), lds_bytes, stream, a, g);

@@ -56,7 +56,7 @@ struct Plan {
     FastDiv d_ow, d_oh, d_rs, d_s, d_ohow, d_tiles_m, d_tiles, d_tiles_ng, d_kg;
     int bm, bn;                  // chosen tile (host side)
     int kc;                      // reduction elements per chunk: KC, or 36 for the 3 x 3 form of conv_taps_kernel
-    int tstore;                  // conv_taps_kernel: the tile is stored through LDS in runs of 64 pixels per channel
+    int tstore;                  // tap kernels: the tile is stored through LDS in runs of 64 pixels per channel
     int taps;                    // 0: conv_gather_kernel; 9 or 1: conv_taps_kernel for 3 x 3 / 1 x 1; 49 or 25: conv_bigtaps_kernel
     int nwg;                     // conv_taps_kernel: groups of four waves per work-group (1, 2 or 4)
     int rblocks;                 // work-groups per output channel in the split-K reduction
@@ -129,6 +129,38 @@ __device__ __forceinline__ void store_tile(const ConvArgs& p, const Plan& g, con
                     store_quad(p, g, m0 + (wm * MB + mb) * 32 + 8 * q + 4 * h, cog + cl0 + tcol, v, scale, shift);
                 }
             }
+    }
+}
+
+// The same epilogue for one 64 x 64 tile of four waves, through LDS: the tile is written
+// transposed into `t` (64 x 68 floats that no wave reads any more) and leaves in runs of 64
+// consecutive pixels of a channel (256 bytes from 16 lanes) instead of 64 separate 16-byte pieces
+// per store instruction, one per lane and channel.
+constexpr int kRunTileFloats = 64 * 68;
+
+__device__ __forceinline__ void store_tile_runs(const ConvArgs& p, const Plan& g, const f32x16& acc, float* t, int split,
+                                                int tile_n, int m0, int cl0, int cog, int wm, int wn, int r32, int h,
+                                                int tid)
+{
+    constexpr int TS = 68;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        *reinterpret_cast<f32x4*>(t + (wn * 32 + r32) * TS + wm * 32 + 8 * q + 4 * h) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int ch = (tid >> 4) + 16 * k, quad = tid & 15;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(t + ch * TS + 4 * quad);
+        if (g.ksplit > 1) {
+            // partial tile: the workspace is padded to whole tiles
+            stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * 64 + ch) * g.Mpad + m0 + 4 * quad, v);
+        } else if (cl0 + ch < g.Kg) {
+            float scale = 1.f, shift = 0.f;
+            if (p.gamma) bn_constants(p, cog + cl0 + ch, &scale, &shift);
+            store_quad(p, g, m0 + 4 * quad, cog + cl0 + ch, v, scale, shift);
+        }
     }
 }
 
@@ -586,31 +618,7 @@ __global__ __launch_bounds__(256 * NWG) void conv_taps_kernel(const ConvArgs p, 
             for (int r = 0; r < 16; ++r) acc[0][0][r] += glds[o * REGION + (wave * 16 + r) * 64 + lane];
     }
     if (NWG == 1 && MB == 1 && NB == 1 && g.tstore) {
-        // The tile goes through LDS, transposed, so that a store instruction writes runs of 64
-        // consecutive pixels of a channel (256 bytes from 16 lanes) instead of 64 separate
-        // 16-byte pieces, one per lane and channel.  The last iteration ended with a barrier:
-        // the staging buffers are free.
-        constexpr int TS = 68;
-        float* const t = glds;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 v = {acc[0][0][4 * q], acc[0][0][4 * q + 1], acc[0][0][4 * q + 2], acc[0][0][4 * q + 3]};
-            *reinterpret_cast<f32x4*>(t + (wn * 32 + r32) * TS + wm * 32 + 8 * q + 4 * h) = v;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int ch = (tid >> 4) + 16 * k, quad = tid & 15;
-            const f32x4 v = *reinterpret_cast<const f32x4*>(t + ch * TS + 4 * quad);
-            if (g.ksplit > 1) {
-                // partial tile: the workspace is padded to whole tiles
-                stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * 64 + ch) * g.Mpad + m0 + 4 * quad, v);
-            } else if (cl0 + ch < g.Kg) {
-                float scale = 1.f, shift = 0.f;
-                if (p.gamma) bn_constants(p, cog + cl0 + ch, &scale, &shift);
-                store_quad(p, g, m0 + 4 * quad, cog + cl0 + ch, v, scale, shift);
-            }
-        }
+        store_tile_runs(p, g, acc[0][0], glds, split, tile_n, m0, cl0, cog, wm, wn, r32, h, tid);
         return;
     }
     store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
@@ -770,6 +778,11 @@ __global__ __launch_bounds__(256) void conv_bigtaps_kernel(const ConvArgs p, con
     for (int c = c_begin; c < c_end; c += 2) {
         iteration(c, S0{});
         if (c + 1 < c_end) iteration(c + 1, S1{});
+    }
+    if (g.tstore) {
+        // the last iteration ended with a barrier: the staging tile is free
+        store_tile_runs(p, g, acc[0][0], glds, split, tile_n, m0, cl0, cog, wm, wn, r32, h, tid);
+        return;
     }
     store_tile<1, 1>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
