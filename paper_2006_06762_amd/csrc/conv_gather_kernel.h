@@ -73,6 +73,8 @@ __device__ __forceinline__ void bn_constants(const ConvArgs& p, int co, float* s
 // Epilogue of one accumulator quad: registers 4q .. 4q+3 of a lane are pixels mq .. mq+3 of
 // output channel co; scale and shift are that channel's batch-norm constants (used when the
 // call has a fused epilogue).
+__device__ __forceinline__ void store_quad_plain(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v);
+
 __device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v, float scale,
                                            float shift)
 {
@@ -80,6 +82,12 @@ __device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = fmaxf(fmaf(v[r], scale, shift), 0.f);
     }
+    store_quad_plain(p, g, mq, co, v);
+}
+
+// The four values as they are: pixels mq .. mq+3 of output channel co.
+__device__ __forceinline__ void store_quad_plain(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v)
+{
     if (g.vec_store) {
         if (mq < g.Mtot) {
             const int n = g.d_ohow.div(mq), pix = mq - n * g.ohow;
@@ -143,9 +151,20 @@ __device__ __forceinline__ void store_tile_runs(const ConvArgs& p, const Plan& g
                                                 int tid)
 {
     constexpr int TS = 68;
+    // the fused epilogue here, where a lane is one channel: its constants once per lane
+    const bool fused = g.ksplit == 1 && p.gamma;
+    float scale = 1.f, shift = 0.f;
+    if (fused) {
+        const int col = cl0 + wn * 32 + r32;
+        bn_constants(p, cog + (col < g.Kg ? col : g.Kg - 1), &scale, &shift);
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        if (fused) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = fmaxf(fmaf(v[r], scale, shift), 0.f);
+        }
         *reinterpret_cast<f32x4*>(t + (wn * 32 + r32) * TS + wm * 32 + 8 * q + 4 * h) = v;
     }
     __syncthreads();
@@ -157,9 +176,7 @@ __device__ __forceinline__ void store_tile_runs(const ConvArgs& p, const Plan& g
             // partial tile: the workspace is padded to whole tiles
             stg4(p.ws + ((int64_t)split * g.Kpad + tile_n * 64 + ch) * g.Mpad + m0 + 4 * quad, v);
         } else if (cl0 + ch < g.Kg) {
-            float scale = 1.f, shift = 0.f;
-            if (p.gamma) bn_constants(p, cog + cl0 + ch, &scale, &shift);
-            store_quad(p, g, m0 + 4 * quad, cog + cl0 + ch, v, scale, shift);
+            store_quad_plain(p, g, m0 + 4 * quad, cog + cl0 + ch, v);
         }
     }
 }
