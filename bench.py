@@ -9,6 +9,7 @@ all inputs resident in HBM.  Prints ONE JSON line:
              FLOPs / step time), buffers rotated between steps so that a step does not
              find its inputs in the 256 MB Infinity Cache of the previous one; the K timed
              steps are replayed from a HIP graph of up to 48 steps (--eager: issued from Python);
+             defaults K = 1000, W = 50 (a fifth of a second of GPU time);
   per_op     every operator's own launch time (HIP events on the launch stream around a
              replayed HIP graph of 48 launches), warm (same buffers) and cold (24 rotating
              buffer sets), TFLOP/s against the 157.3 TFLOP/s fp32 MFMA peak and GB/s
@@ -327,8 +328,8 @@ def cpu_baseline(I, host, table):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing and parity check (profiling runs)")
     ap.add_argument("--eager", action="store_true",
@@ -403,6 +404,12 @@ def main():
     # rotating buffer sets) that is replayed K // G times, the remaining K % G steps issued one by
     # one on the same stream; --eager issues all K steps from Python.
     group = 0 if args.eager else (min(args.steps, 48) // 4) * 4
+    if group:
+        # prefer a graph length that divides K, so that no step is left over for the eager tail
+        for cand in range(group, 19, -4):
+            if args.steps % cand == 0:
+                group = cand
+                break
     if group:
         stream = torch.cuda.Stream()
         stream.wait_stream(torch.cuda.current_stream())
