@@ -109,7 +109,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     // tiles stored in runs of 64 pixels per channel (1 x 1 layers, 56 x 56 and 28 x 28 maps at batch 16:
     // 3-4 % faster than one 16-byte piece per lane and channel; the 7 x 7 stem at batch 16, which writes
     // 51 MB: 7 %; partial tiles of a split reduction, whose workspace is padded and aligned: 1-2 %)
-    g->tstore = g->taps != 0 && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
+    g->tstore = (g->taps != 0 || (bm == 64 && bn == 64)) && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
     g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
     g->d_rblocks = make_fastdiv(g->rblocks);
 }

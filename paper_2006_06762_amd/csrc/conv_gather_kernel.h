@@ -414,6 +414,11 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(const ConvArgs p, cons
         if (c + 1 < c_end) iteration(c + 1, S1{});
     }
 
+    if (MB == 1 && NB == 1 && g.tstore) {
+        // the last iteration ended with a barrier: the staging buffers are free
+        store_tile_runs(p, g, acc[0][0], glds, split, tile_n, m0, cl0, cog, wm, wn, r32, h, tid);
+        return;
+    }
     store_tile<MB, NB>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
 
