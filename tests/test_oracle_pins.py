@@ -6,6 +6,8 @@ reductions of one operator to another, and a second, differently written
 evaluation (numpy einsum / explicit padding and window slicing) on small
 shapes.  Each test names the plausible mistake it would catch.
 """
+import math
+
 import numpy as np
 import pytest
 
@@ -489,6 +491,35 @@ def test_tbs_rows_are_softmax_of_tbg():
     # (closed form) -- uniform scores give exactly 1/S
     z = np.zeros_like(q)
     assert np.array_equal(oracle.tbs(z, k), np.full_like(p, 1.0 / 6))
+
+
+def test_tbs_two_keys_is_the_logistic_function():
+    # S = 2: softmax over two scores is 1 / (1 + exp(-(s_j - s_other))), written out by hand
+    B, S, H, D = 1, 2, 1, 3
+    q = np.array([[[[1.0, 2.0, -1.0]], [[0.5, 0.0, 2.0]]]], dtype=np.float32).reshape(B, S, H, D)
+    k = np.array([[[[0.25, -1.0, 0.5]], [[1.0, 1.0, 1.0]]]], dtype=np.float32).reshape(B, S, H, D)
+    p = oracle.tbs(q, k)
+    for i in range(S):
+        s0 = float(sum(float(q[0, i, 0, d]) * float(k[0, 0, 0, d]) for d in range(D)))
+        s1 = float(sum(float(q[0, i, 0, d]) * float(k[0, 1, 0, d]) for d in range(D)))
+        assert abs(p[0, 0, i, 0] - 1.0 / (1.0 + math.exp(s1 - s0))) < 1e-15
+        assert abs(p[0, 0, i, 1] - 1.0 / (1.0 + math.exp(s0 - s1))) < 1e-15
+
+
+def test_tbs_large_scores_do_not_overflow():
+    # scores near 1600: exp overflows a double unless the row maximum is subtracted first; the
+    # softmax of (1600, 1599, 0) is (1, e^-1, e^-1600) / (1 + e^-1 + e^-1600); all inputs exact in fp32
+    B, S, H, D = 1, 3, 1, 2
+    q = np.zeros((B, S, H, D), dtype=np.float32)
+    q[0, :, 0, 0] = 32.0
+    k = np.zeros((B, S, H, D), dtype=np.float32)
+    k[0, :, 0, 0] = [50.0, 49.96875, 0.0]
+    p = oracle.tbs(q, k)
+    assert np.isfinite(p).all()
+    z = 1.0 + math.exp(-1.0)
+    want = np.array([1.0 / z, math.exp(-1.0) / z, 0.0])
+    for i in range(S):
+        np.testing.assert_allclose(p[0, 0, i], want, rtol=0, atol=1e-15)
 
 
 # ---------------------------------------------------------------- NRM
