@@ -177,9 +177,8 @@ typedef struct {
 
 /* NRM (Sec. 7.1, Appendix C "NRM"; Sec. 4.1 names it as the operator with
  * parallelism only in its reduction): out[b] = sqrt(sum_{i,j} x[b,i,j]^2),
- * `batch` device floats.  Larger matrices (more than 16 K elements; more than
- * 64 K for batches of at most 16 or at least 256) are reduced in slices whose
- * partial sums pass through `ws` (anr_workspace_size tells how much); the sum
+ * `batch` device floats.  Matrices of more than 16 K elements are reduced in
+ * slices whose partial sums pass through `ws` (anr_workspace_size); the sum
  * order is fixed, so results do not vary from run to run. */
 anr_status anr_nrm(const anr_nrm_desc *desc, const float *x, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);

@@ -96,11 +96,6 @@ __global__ __launch_bounds__(kNT) void nrm_final_kernel(const NrmArgs p, int par
 int nrm_parts(const NrmArgs& a)
 {
     const int64_t total = a.N * a.M;
-    // up to 64 K elements one work-group per matrix finishes the job in one launch: two rounds of
-    // eight loads per thread cost less than the second kernel, unless the batch is of a size that
-    // leaves most CUs without a work-group (256 x 256: 4.4 -> 4.2 us at batch 1, 5.6 -> 5.2 at 16,
-    // 16.0 -> 14.3 at 256, but 6.9 -> 7.9 at 64)
-    if (total <= 65536 && (a.batch <= 16 || a.batch >= 256)) return 1;
     int64_t want = (2048 + a.batch - 1) / a.batch;
     const int64_t most = (total + 16383) / 16384;
     if (want > most) want = most;

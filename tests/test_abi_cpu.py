@@ -177,11 +177,6 @@ def test_nrm_validation():
     need = B.workspace_size(B.ANR_OP_NRM, big)
     assert need == 4 * 1024                                             # 16 M elements in 1024 slices
     assert lib.anr_nrm(ctypes.byref(big), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_WORKSPACE
-    # up to 64 K elements a matrix is one slice (no workspace) for small and for large batches;
-    # in between, and above 64 K elements, it is cut into slices of at least 16 K elements
-    for batch, slices in ((1, 1), (16, 1), (64, 4), (256, 1)):
-        assert B.workspace_size(B.ANR_OP_NRM, B.NrmDesc(256, 256, 256, batch, 65536)) == (0 if slices == 1 else 4 * slices * batch)
-    assert B.workspace_size(B.ANR_OP_NRM, B.NrmDesc(512, 512, 512, 1, 0)) == 4 * 16
 
 
 def test_workspace_size():
