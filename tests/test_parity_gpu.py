@@ -865,7 +865,8 @@ NRM_TOL = 2e-6      # relative: fp32 partial sums of at most a few thousand squa
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (1, 33, 7), (1, 256, 256), (3, 100, 37), (16, 512, 512),
-                                   (1, 1000, 1000), (2, 2048, 1024), (1, 4096, 4096)], ids=str)
+                                   (1, 1000, 1000), (2, 2048, 1024), (1, 4096, 4096), (16, 256, 256), (64, 256, 256),
+                                   (256, 250, 260)], ids=str)
 def test_nrm(anr, shape):
     b, N, M = shape
     x = I.uniform(np.random.Generator(np.random.PCG64(700 + N)), (b, N, M))
