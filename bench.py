@@ -36,6 +36,14 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 2.4 GHz x 256 flop/clk/CU
 PEAK_HBM_GBS = 8000.0
 METRIC = "achieved TFLOP/s and % of fp32 MFMA peak per operator; DEP HBM GB/s"
+# the paper's own headline figures, printed beside the throughput as context (other hardware,
+# other baselines: not a target and not comparable with `value`)
+PAPER_CONTEXT = {
+    "source": "arXiv 2006.06762, abstract and Sec. 7.3",
+    "claim": "speed-up of the generated programs over the prior state of the art, up to",
+    "intel_cpu": 3.8, "arm_cpu": 2.6, "nvidia_gpu": 1.7, "unit": "x",
+}
+MIN_TIMED_MS = 50.0               # the timed region lasts at least this long, whatever --steps is
 
 
 def conv_flops(s):
@@ -338,6 +346,10 @@ def main():
                     help="skip the extra timing of the step with its operators on three streams (profiling runs: "
                          "keeps every kernel's launches free of other kernels)")
     ap.add_argument("--only", default=None, help="profiling aid: launch only this operator in the step")
+    ap.add_argument("--cold-only", action="store_true",
+                    help="profiling aid: every launch of the run reads buffers that are not in the caches (24 sets in "
+                         "rotation everywhere, no warm or eager per-operator timing), so that a kernel trace of the "
+                         "run holds cold launches only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -390,21 +402,35 @@ def main():
     NSETS = 24
     sets = [OpSet(anr, I, torch, host) for _ in range(NSETS)]
 
+    # a whole step moves ~135 MB, so four sets in rotation keep it out of the caches; one operator
+    # alone (--only) moves ~25 MB and rotates all 24
+    rot = 4 if args.only is None else NSETS
+
     def step(i):
-        s = sets[i % 4]
+        s = sets[i % rot]
         for n in names:
             s.run(n)
 
+    t0 = time.perf_counter()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    est_ms = (time.perf_counter() - t0) * 1000.0 / max(1, args.warmup)
+    # K steps make one round; short runs time several rounds so that the timed region is not a
+    # single graph replay of a few milliseconds
+    rounds = 1 if args.warmup == 0 else max(1, int(np.ceil(MIN_TIMED_MS / max(1e-3, est_ms * args.steps))))
     # The timed K steps.  Several kernels of a step run 6-9 us, less than it takes Python to issue
     # a launch, so the GPU waits for the host now and then (about 2.5 % of a step).  By default
     # the steps are therefore captured in a HIP graph of up to 48 steps (a multiple of the 4
     # rotating buffer sets) that is replayed K // G times, the remaining K % G steps issued one by
     # one on the same stream; --eager issues all K steps from Python.
-    group = 0 if args.eager else (min(args.steps, 48) // 4) * 4
-    if group:
+    if args.eager:
+        group = 0
+    elif rot == 4:
+        group = (min(args.steps, 48) // 4) * 4
+    else:
+        group = (min(args.steps, 2 * rot) // rot) * rot
+    if group and rot == 4:
         # prefer a graph length that divides K, so that no step is left over for the eager tail
         for cand in range(group, 19, -4):
             if args.steps % cand == 0:
@@ -422,21 +448,23 @@ def main():
             stream.synchronize()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps // group):
-                graph.replay()
-            for i in range(args.steps % group):
-                step(i)
+            for _ in range(rounds):
+                for _ in range(args.steps // group):
+                    graph.replay()
+                for i in range(args.steps % group):
+                    step(i)
             stream.synchronize()
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
         torch.cuda.current_stream().wait_stream(stream)
     else:
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            step(i)
+        for _ in range(rounds):
+            for i in range(args.steps):
+                step(i)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-    ms_per_step = wall * 1000.0 / args.steps
+    ms_per_step = wall * 1000.0 / (args.steps * rounds)
     step_flops = sum(table[n][0] for n in names)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -447,12 +475,15 @@ def main():
         flops, nbytes, bound = table[n]
         reps = 200
         for i in range(10):
-            sets[0].run(n)
+            sets[i % NSETS if args.cold_only else 0].run(n)
         # launches captured in a HIP graph: kernel time plus the GPU's own kernel-to-kernel gap
-        warm = time_graph(torch, lambda i: sets[0].run(n), 2 * NSETS)
         cold = time_graph(torch, lambda i: sets[i % NSETS].run(n), 2 * NSETS)
-        # the same launches issued one by one from Python (adds host launch overhead)
-        eager = time_launches(torch, lambda i: sets[i % NSETS].run(n), reps)
+        if args.cold_only:
+            warm = eager = float("nan")
+        else:
+            warm = time_graph(torch, lambda i: sets[0].run(n), 2 * NSETS)
+            # the same launches issued one by one from Python (adds host launch overhead)
+            eager = time_launches(torch, lambda i: sets[i % NSETS].run(n), reps)
         rec = {"op": n, "bound": bound, "flops": flops, "bytes": nbytes,
                "us_warm": warm, "us_cold": cold, "us_cold_eager": eager,
                "tflops_warm": flops / warm / 1e6, "tflops_cold": flops / cold / 1e6,
@@ -465,6 +496,8 @@ def main():
 
     by = {r["op"]: r for r in per_op}
     dom = by.get("C2D_S2") or per_op[0]
+    # HBM traffic per launch is a stored figure (two rocprofv3 --pmc runs, kept under profiles/),
+    # not something this run measures
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -472,6 +505,7 @@ def main():
             traffic = json.load(open(tpath)).get(dom["op"])
         except Exception:
             traffic = None
+    traffic_source = "stored: profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)" if traffic else None
     # the kernel behind each operator's benchmark launch (with --only, the roofline is that operator's)
     kernels = {"GMM": "gemm_tile32_ksplit_kernel", "C2D": "conv_igemm_kernel", "ConvLayer": "conv_igemm_kernel",
                "C2D_S2": "conv_igemm_kernel", "TBG": "tbg_tile64_kernel", "TBS": "tbs_rows32_kernel",
@@ -480,14 +514,15 @@ def main():
         roofline = {
             "kernel": "%s (%s launch)" % (kernels.get(dom["op"], "?"), dom["op"]), "bound": "hbm",
             "achieved": dom["gbs_cold"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": dom["gbs_cold"] / PEAK_HBM_GBS, "traffic": traffic, "launch_us": dom["us_cold"],
+            "frac": dom["gbs_cold"] / PEAK_HBM_GBS, "traffic": traffic, "traffic_source": traffic_source,
+            "launch_us": dom["us_cold"],
         }
     else:
         roofline = {
             "kernel": "%s (%s launch)" % (kernels.get(dom["op"], "?"), dom["op"]), "bound": "mfma",
             "achieved": dom["tflops_cold"], "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
             "frac": dom["tflops_cold"] / PEAK_MFMA_F32_TFLOPS, "traffic": traffic,
-            "launch_us": dom["us_cold"],
+            "traffic_source": traffic_source, "launch_us": dom["us_cold"],
         }
 
     out = {
@@ -499,8 +534,10 @@ def main():
                                "3x3+BN+ReLU + TBG B16 S128 H12 D64 + DEP N16 C256 28^2 3x3 + C2D N16 256->512 "
                                "28^2 3x3 s2 (all BASELINE configs, fp32)" if args.only is None
                    else "only " + args.only,
-                   "step_gflop": step_flops / 1e9, "buffer_sets_rotated": 4,
-                   "steps_per_graph_replay": group},
+                   "step_gflop": step_flops / 1e9, "buffer_sets_rotated": rot,
+                   "steps_per_graph_replay": group, "timed_rounds_of_k_steps": rounds,
+                   "timed_steps": args.steps * rounds},
+        "paper_context": PAPER_CONTEXT,
         "roofline": roofline,
         "peaks": {"mfma_f32_tflops": PEAK_MFMA_F32_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
         "per_op": per_op,
@@ -538,6 +575,9 @@ def main():
         out["max_rel_err_vs_oracle"] = errs
         out["parity_ok"] = all(e <= 1e-4 for e in errs.values())
     print(json.dumps(out))
+    if out.get("parity_ok") is False:
+        print("bench.py: parity against the oracle FAILED: %s" % out["max_rel_err_vs_oracle"], file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -20,9 +20,11 @@
  *     vectorised kernels; anything else runs a slower kernel with the same
  *     results.
  *   - `ws`/`ws_bytes` is a device workspace owned by the caller, 16-byte
- *     aligned.  anr_workspace_size() says how many bytes an operation may
- *     want for a descriptor (a figure that depends on the descriptor only,
- *     not on pointer alignment); ws may be NULL when that is 0.  Two
+ *     aligned.  anr_workspace_size() says how many bytes an operation needs
+ *     for a descriptor; the figure depends on the descriptor only (it is the
+ *     need of the plan for 16-byte aligned pointers, the one
+ *     anr_conv2d_route reports; a call whose pointers are less aligned runs
+ *     kernels that need no workspace); ws may be NULL when it is 0.  Two
  *     operations use one: the convolutions for shapes with few output tiles
  *     and a long reduction (batch 1, 7x7 maps), whose reduction is split
  *     over work-groups that leave partial tiles there, and anr_nrm for the
@@ -32,8 +34,11 @@
  *     must be ordered (same stream).
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is launched, so an invalid call has no effect on the device.
- *   - Thread-safe and re-entrant: the only state is a thread-local copy of the last
- *     HIP launch error, kept for anr_last_hip_error().
+ *   - Thread-safe and re-entrant.  The library reads no environment variable
+ *     and no configuration file: what a call does follows from its arguments
+ *     alone.  The only state is a thread-local copy of the last HIP launch
+ *     error, kept for anr_last_hip_error(), and a once-per-device note that a
+ *     kernel's shared-memory limit has been raised (idempotent).
  */
 #ifndef ANR_H
 #define ANR_H
@@ -49,7 +54,8 @@ typedef enum {
     ANR_OK = 0,
     ANR_ERR_NULL = 1,         /* a required pointer is NULL                        */
     ANR_ERR_INVALID_ARG = 2,  /* non-positive extent, bad stride, empty output ... */
-    ANR_ERR_UNSUPPORTED = 3,  /* valid but not implemented (dilation, layout)      */
+    ANR_ERR_UNSUPPORTED = 3,  /* valid but not implemented (layout, w-stride != 1,
+                                 extents beyond the kernels' index range)          */
     ANR_ERR_WORKSPACE = 4,    /* ws_bytes smaller than anr_workspace_size()        */
     ANR_ERR_LAUNCH = 5        /* the HIP runtime refused the launch                */
 } anr_status;
@@ -97,7 +103,19 @@ typedef struct {
  *   layout must be ANR_LAYOUT_NCHW (else ANR_ERR_UNSUPPORTED).  pad >= 0,
  *   stride >= 1, dil >= 1; pad < kernel extent is NOT required.  OH <= 0 or
  *   OW <= 0 is ANR_ERR_INVALID_ARG.
+ *   route (an anr_conv_route_choice; any other value is ANR_ERR_INVALID_ARG)
+ *   selects between the library's two families of convolution kernels:
+ *   ANR_CONV_ROUTE_AUTO lets the library choose by shape; ANR_CONV_ROUTE_PATCH
+ *   asks for the 3x3 patch-staging kernel whenever it can run the shape and
+ *   pointers at all (it has no split of the reduction over work-groups, so it
+ *   is slow when there are few output tiles); ANR_CONV_ROUTE_GENERAL never
+ *   uses it.  Results agree to rounding whatever the route; anr_workspace_size
+ *   and anr_conv2d_route follow the field.  The depthwise call ignores it.
  */
+typedef enum {
+    ANR_CONV_ROUTE_AUTO = 0, ANR_CONV_ROUTE_PATCH = 1, ANR_CONV_ROUTE_GENERAL = 2
+} anr_conv_route_choice;
+
 typedef struct {
     int32_t N, C, H, W;
     int32_t K, R, S;
@@ -108,7 +126,7 @@ typedef struct {
     int64_t x_stride[4];
     int64_t y_stride[4];
     int32_t groups;      /* 0 or 1: ordinary convolution */
-    int32_t reserved;    /* must be 0 */
+    int32_t route;       /* anr_conv_route_choice; 0: the library chooses */
 } anr_conv_desc;
 
 /*
@@ -183,10 +201,10 @@ typedef struct {
 anr_status anr_nrm(const anr_nrm_desc *desc, const float *x, float *out,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Bytes of device workspace `op` (an anr_op) may want for `desc` (the matching
- * descriptor type): an upper bound that depends on the shape only, not on
- * pointer alignment.  Writes 0 when none is needed.  Validates the descriptor
- * the same way the operation does. */
+/* Bytes of device workspace `op` (an anr_op) needs for `desc` (the matching
+ * descriptor type): a function of the descriptor only, enough for any pointer
+ * alignment.  Writes 0 when none is needed.  Validates the descriptor the same
+ * way the operation does. */
 anr_status anr_workspace_size(int op, const void *desc, size_t *bytes);
 
 /* Which kernel anr_conv2d / anr_conv_bn_relu would run for `desc` with 16-byte aligned
@@ -208,7 +226,7 @@ typedef struct {
     int32_t ksplit;                /* 1: no split                                                 */
     int32_t wave_groups;           /* 1, 2 or 4                                                   */
     int32_t work_groups;           /* launched by the main kernel                                 */
-    uint64_t workspace_bytes;      /* what this plan needs (<= anr_workspace_size)                */
+    uint64_t workspace_bytes;      /* what this plan needs (== anr_workspace_size)                */
 } anr_conv_route;
 anr_status anr_conv2d_route(const anr_conv_desc *desc, anr_conv_route *route);
 

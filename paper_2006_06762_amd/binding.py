@@ -47,7 +47,7 @@ class ConvDesc(ctypes.Structure):
                 ("dil_h", ctypes.c_int32), ("dil_w", ctypes.c_int32),
                 ("layout", ctypes.c_int32),
                 ("x_stride", ctypes.c_int64 * 4), ("y_stride", ctypes.c_int64 * 4),
-                ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("groups", ctypes.c_int32), ("route", ctypes.c_int32)]
 
 
 class ConvRoute(ctypes.Structure):
@@ -56,6 +56,7 @@ class ConvRoute(ctypes.Structure):
                 ("workspace_bytes", ctypes.c_uint64)]
 
 
+ANR_CONV_ROUTE_AUTO, ANR_CONV_ROUTE_PATCH, ANR_CONV_ROUTE_GENERAL = 0, 1, 2
 ANR_CONV_KERNEL_PATCH, ANR_CONV_KERNEL_TAPS, ANR_CONV_KERNEL_BIGTAPS, ANR_CONV_KERNEL_GATHER, \
     ANR_CONV_KERNEL_DIRECT = 1, 2, 3, 4, 5
 
@@ -134,10 +135,11 @@ def _stream():
 
 
 def conv_desc(x_shape, K, R, S, stride=(1, 1), pad=(0, 0), x_stride=None, y_stride=None, dil=(1, 1),
-              layout=ANR_LAYOUT_NCHW, groups=1) -> ConvDesc:
+              layout=ANR_LAYOUT_NCHW, groups=1, route=ANR_CONV_ROUTE_AUTO) -> ConvDesc:
     N, C, H, W = x_shape
     d = ConvDesc(N, C, H, W, K, R, S, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], layout)
     d.groups = groups
+    d.route = route
     if x_stride is not None:
         d.x_stride = (ctypes.c_int64 * 4)(*x_stride)
     if y_stride is not None:
@@ -207,26 +209,29 @@ def _conv_strides(t):
     return None if t.is_contiguous() else tuple(t.stride())
 
 
-def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1):
+def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1, route=ANR_CONV_ROUTE_AUTO):
     """y = conv2d(x, w); x [N,C,H,W], w [K,C/groups,R,S] packed, y [N,K,OH,OW] (may be strided views).
     ws: optional workspace tensor of at least workspace_size(ANR_OP_CONV2D, desc) bytes."""
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
-    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups)
+    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups,
+                  route=route)
     wp, wb = _workspace(ANR_OP_CONV2D, d, ws)
     _check(_lib.anr_conv2d(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), wp, wb, _stream()), "anr_conv2d")
     return y
 
 
-def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1):
+def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1,
+                 route=ANR_CONV_ROUTE_AUTO):
     K, _, R, S = w.shape
     if not w.is_contiguous():
         raise ValueError("weights must be packed")
     for v in (gamma, beta, mean, var):
         if tuple(v.shape) != (K,) or not v.is_contiguous():
             raise ValueError("batch-norm vectors must be packed [K]")
-    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups)
+    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups,
+                  route=route)
     wp, wb = _workspace(ANR_OP_CONV_BN_RELU, d, ws)
     _check(_lib.anr_conv_bn_relu(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(gamma), _ptr(beta), _ptr(mean),
                                  _ptr(var), ctypes.c_float(eps), _ptr(y), wp, wb, _stream()),

@@ -3,6 +3,7 @@
 Run as ``python -m paper_2006_06762_amd.build`` (hipcc cross-compiles without a GPU).
 """
 import os
+import shutil
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -50,10 +51,27 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def _stale() -> bool:
+    """True when the library is missing or older than any source it is built from."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    srcs = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    inc = os.path.join(ROOT, "include")
+    srcs += [os.path.join(inc, f) for f in os.listdir(inc)]
+    return any(os.path.getmtime(f) > built for f in srcs if os.path.isfile(f))
+
+
 def ensure_built(verbose: bool = False) -> str:
-    """Build the library only if no built one is there (tests, the smoke run and the benchmark
-    load what is built; after a change to a source, build again explicitly)."""
-    return LIB if os.path.exists(LIB) else build(verbose=verbose)
+    """Build the library unless a built one is there that is newer than every file under
+    csrc/ and include/ (tests, the smoke run and the benchmark load what is built)."""
+    if not _stale():
+        return LIB
+    if not shutil.which("hipcc"):
+        if os.path.exists(LIB):
+            return LIB      # a box without the compiler runs what was shipped
+        raise RuntimeError("libanr.so is missing and hipcc is not on PATH")
+    return build(verbose=verbose)
 
 
 if __name__ == "__main__":

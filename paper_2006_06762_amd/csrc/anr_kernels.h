@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace anr {
 
 template <typename T>
@@ -24,6 +26,28 @@ inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, s
 }
 
 inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Dynamic shared-memory limit already granted to one kernel, per device.  The runtime call
+// that raises it costs microseconds (more than some of the kernels run), so a launcher keeps
+// one of these per kernel instantiation and calls the runtime only when a launch needs more
+// than any earlier one on that device.  Setting the attribute twice is harmless, so a race
+// between two threads costs one redundant call and nothing else.
+struct LdsLimit {
+    static constexpr int kDevices = 16;
+    std::atomic<int> bytes[kDevices];
+};
+
+inline hipError_t raise_lds_limit(const void* kernel, size_t bytes, LdsLimit& lim)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < LdsLimit::kDevices;
+    if (tracked && lim.bytes[dev].load(std::memory_order_acquire) >= (int)bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && tracked) lim.bytes[dev].store((int)bytes, std::memory_order_release);
+    return e;
+}
 
 // Batched C = A.B (B_IS_NK false: B is K x N, row stride ldb) or C = A.B^T
 // (B_IS_NK true: B is N x K, row stride ldb).  Batch index z in [0, batch) is
@@ -55,6 +79,7 @@ struct ConvArgs {
     int stride_h, stride_w, pad_h, pad_w;
     int dil_h, dil_w;
     int groups;      // >= 1; weights are [K, C/groups, R, S] (ignored by the depthwise launchers)
+    int route;       // the descriptor's anr_conv_route_choice: 0 library's choice, 1 patch kernel, 2 general
     int OH, OW;
     int64_t xs[4];   // element strides n,c,h,w (w stride is 1)
     int64_t ys[4];
@@ -68,10 +93,12 @@ struct ConvArgs {
     float* ws;
     size_t ws_bytes;
 };
-// Workspace the convolution of `a` needs (0 for most shapes); a launch with less fails with
-// hipErrorInvalidValue before anything is enqueued.
+// Workspace the convolution of `a` needs (0 for most shapes): that of the plan for 16-byte
+// aligned x and w (null pointers count as aligned); plans for less aligned pointers need none.
 size_t conv2d_workspace_bytes(const ConvArgs& a);
-hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream);
+// Plans once, checks a.ws / a.ws_bytes against the plan, launches.  *ws_fault: 0 fine, 1 the
+// workspace is missing or too small, 2 it is not 16-byte aligned (nothing is enqueued then).
+hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault);
 hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
 
 // out[b] = sqrt(sum of squares of the N x M matrix b); rows `ld` apart, matrices `stride` apart.

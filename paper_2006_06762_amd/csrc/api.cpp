@@ -10,7 +10,7 @@
 
 namespace {
 
-constexpr int kVersion = 200;   // 0.1.0
+constexpr int kVersion = 300;   // 0.3.0
 
 // HIP status of the most recent failed launch made by this thread (diagnostics only).
 thread_local int g_last_hip_error = 0;
@@ -38,7 +38,9 @@ anr_status check_conv(const anr_conv_desc* d, bool depthwise, ConvGeom* g)
     if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return ANR_ERR_INVALID_ARG;
     if (d->dil_h < 1 || d->dil_w < 1) return ANR_ERR_INVALID_ARG;
     if (depthwise && d->K != d->C) return ANR_ERR_INVALID_ARG;
-    if (d->groups < 0 || d->reserved != 0) return ANR_ERR_INVALID_ARG;
+    if (d->groups < 0) return ANR_ERR_INVALID_ARG;
+    if (d->route != ANR_CONV_ROUTE_AUTO && d->route != ANR_CONV_ROUTE_PATCH && d->route != ANR_CONV_ROUTE_GENERAL)
+        return ANR_ERR_INVALID_ARG;
     if (!depthwise && d->groups > 1 && (d->C % d->groups != 0 || d->K % d->groups != 0)) return ANR_ERR_INVALID_ARG;
     if (d->layout != ANR_LAYOUT_NCHW) return ANR_ERR_UNSUPPORTED;
     const int64_t eh = (int64_t)d->H + 2 * (int64_t)d->pad_h - (int64_t)d->dil_h * (d->R - 1) - 1;
@@ -88,6 +90,7 @@ anr::ConvArgs make_conv_args(const anr_conv_desc* d, const ConvGeom& g, const fl
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.dil_h = d->dil_h; a.dil_w = d->dil_w;
     a.groups = d->groups > 1 ? d->groups : 1;
+    a.route = d->route;
     a.OH = g.OH; a.OW = g.OW;
     for (int i = 0; i < 4; ++i) { a.xs[i] = g.xs[i]; a.ys[i] = g.ys[i]; }
     a.gamma = a.beta = a.mean = a.var = nullptr;
@@ -97,16 +100,17 @@ anr::ConvArgs make_conv_args(const anr_conv_desc* d, const ConvGeom& g, const fl
     return a;
 }
 
-// Attaches the caller's workspace; fails when the convolution needs more than it holds.
-anr_status attach_workspace(anr::ConvArgs* a, void* ws, size_t ws_bytes)
+// Hands the caller's workspace to the launcher, which plans the call once and reports whether
+// the plan's need is met (nothing is enqueued when it is not).
+anr_status run_conv2d(anr::ConvArgs* a, void* ws, size_t ws_bytes, void* hip_stream)
 {
-    const size_t need = anr::conv2d_workspace_bytes(*a);
-    if (need == 0) return ANR_OK;
-    if (!ws || ws_bytes < need) return ANR_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(ws) & 15) return ANR_ERR_INVALID_ARG;
     a->ws = static_cast<float*>(ws);
-    a->ws_bytes = ws_bytes;
-    return ANR_OK;
+    a->ws_bytes = ws ? ws_bytes : 0;
+    int ws_fault = 0;
+    const hipError_t e = anr::launch_conv2d(*a, static_cast<hipStream_t>(hip_stream), &ws_fault);
+    if (ws_fault == 1) return ANR_ERR_WORKSPACE;
+    if (ws_fault == 2) return ANR_ERR_INVALID_ARG;
+    return launch_status(e);
 }
 
 anr_status check_gemm(const anr_gemm_desc* d)
@@ -115,9 +119,12 @@ anr_status check_gemm(const anr_gemm_desc* d)
     if (d->M < 1 || d->N < 1 || d->K < 1 || d->batch < 1) return ANR_ERR_INVALID_ARG;
     if (d->lda < d->K || d->ldb < d->N || d->ldc < d->N) return ANR_ERR_INVALID_ARG;
     if (d->strideA < 0 || d->strideB < 0 || d->strideC < 0) return ANR_ERR_INVALID_ARG;
-    if (d->batch > 1 && d->strideC < (d->M - 1) * d->ldc + d->N) return ANR_ERR_INVALID_ARG;
-    const int64_t lim = (int64_t)1 << 31;
+    // extents the kernels' 32-bit tile arithmetic takes (and small enough that the products
+    // below and in the launchers cannot overflow 64 bits)
+    const int64_t lim = (int64_t)1 << 30;
     if (d->M >= lim || d->N >= lim || d->K >= lim) return ANR_ERR_UNSUPPORTED;
+    if (d->lda >= 2 * lim || d->ldb >= 2 * lim || d->ldc >= 2 * lim) return ANR_ERR_UNSUPPORTED;
+    if (d->batch > 1 && d->strideC < (d->M - 1) * d->ldc + d->N) return ANR_ERR_INVALID_ARG;
     if (d->batch > 65535) return ANR_ERR_UNSUPPORTED;              // grid z limit
     if ((d->M + 63) / 64 > 65535) return ANR_ERR_UNSUPPORTED;       // grid y limit
     return ANR_OK;
@@ -150,7 +157,11 @@ anr_status check_tbg(const anr_tbg_desc* d, bool softmax, TbgGeom* g)
         for (int i = 0; i < 4; ++i) outs[t][i] = ins[t][i];
     }
     // the output view must not overlap itself: rows inside matrices inside heads inside batches
-    if (g->os[2] < d->S) return ANR_ERR_INVALID_ARG;
+    const int64_t S = d->S;
+    if (g->os[2] < S) return ANR_ERR_INVALID_ARG;
+    if (g->os[2] >= ((int64_t)1 << 40) || g->os[1] >= ((int64_t)1 << 50)) return ANR_ERR_UNSUPPORTED;
+    if (g->os[1] < (S - 1) * g->os[2] + S) return ANR_ERR_INVALID_ARG;
+    if (g->os[0] < (d->H - 1) * g->os[1] + (S - 1) * g->os[2] + S) return ANR_ERR_INVALID_ARG;
     if ((int64_t)d->B * d->H > 65535) return ANR_ERR_UNSUPPORTED;
     if (softmax && d->S > 1024) return ANR_ERR_UNSUPPORTED;
     return ANR_OK;
@@ -181,7 +192,10 @@ anr_status check_nrm(const anr_nrm_desc* d, anr::NrmArgs* a)
     if (!d) return ANR_ERR_NULL;
     if (d->N < 1 || d->M < 1 || d->batch < 1 || d->ld < d->M || d->stride < 0) return ANR_ERR_INVALID_ARG;
     if (d->batch > 65535) return ANR_ERR_UNSUPPORTED;
-    if (d->N >= ((int64_t)1 << 31) || d->M >= ((int64_t)1 << 31)) return ANR_ERR_UNSUPPORTED;
+    if (d->N >= ((int64_t)1 << 31) || d->M >= ((int64_t)1 << 31) || d->ld >= ((int64_t)1 << 32))
+        return ANR_ERR_UNSUPPORTED;
+    // matrices of a batch must not overlap (stride 0: the same matrix every time)
+    if (d->batch > 1 && d->stride != 0 && d->stride < (d->N - 1) * d->ld + d->M) return ANR_ERR_INVALID_ARG;
     a->N = d->N; a->M = d->M; a->ld = d->ld; a->stride = d->stride;
     a->batch = (int)d->batch;
     return ANR_OK;
@@ -218,9 +232,7 @@ anr_status anr_conv2d(const anr_conv_desc* d, const float* x, const float* w, fl
     if (st != ANR_OK) return st;
     if (!x || !w || !y) return ANR_ERR_NULL;
     anr::ConvArgs a = make_conv_args(d, g, x, w, y);
-    st = attach_workspace(&a, ws, ws_bytes);
-    if (st != ANR_OK) return st;
-    return launch_status(anr::launch_conv2d(a, static_cast<hipStream_t>(hip_stream)));
+    return run_conv2d(&a, ws, ws_bytes, hip_stream);
 }
 
 anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float* w, const float* gamma,
@@ -234,9 +246,7 @@ anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float*
     if (!x || !w || !y || !gamma || !beta || !mean || !var) return ANR_ERR_NULL;
     anr::ConvArgs a = make_conv_args(d, g, x, w, y);
     a.gamma = gamma; a.beta = beta; a.mean = mean; a.var = var; a.eps = eps;
-    st = attach_workspace(&a, ws, ws_bytes);
-    if (st != ANR_OK) return st;
-    return launch_status(anr::launch_conv2d(a, static_cast<hipStream_t>(hip_stream)));
+    return run_conv2d(&a, ws, ws_bytes, hip_stream);
 }
 
 anr_status anr_dwconv(const anr_conv_desc* d, const float* x, const float* w, float* y, void* ws,
@@ -305,10 +315,10 @@ anr_status anr_workspace_size(int op, const void* desc, size_t* bytes)
     *bytes = 0;
     if (op == ANR_OP_NRM) *bytes = anr::nrm_workspace_bytes(na);
     if (op == ANR_OP_CONV2D || op == ANR_OP_CONV_BN_RELU) {
-        // an upper bound that does not depend on pointer alignment: what the general kernel's
-        // split-K needs for this shape (the tuned kernel, when it takes the call, needs none)
+        // the need of the plan for 16-byte aligned pointers (what anr_conv2d_route reports); plans
+        // for less aligned pointers never split the reduction and need none
         const anr::ConvArgs a = make_conv_args(static_cast<const anr_conv_desc*>(desc), cg, nullptr, nullptr, nullptr);
-        *bytes = anr::conv2d_gather_workspace_bytes(a);
+        *bytes = anr::conv2d_workspace_bytes(a);
     }
     return ANR_OK;
 }

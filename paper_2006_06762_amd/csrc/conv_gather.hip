@@ -90,6 +90,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     g->tiles_ng = (g->Kg + bn - 1) / bn;
     g->tiles_n = g->groups * g->tiles_ng;
     g->d_tiles_ng = make_fastdiv(g->tiles_ng);
+    if (ks < 1) ks = 1;
     if (ks > g->nchunks) ks = g->nchunks;
     g->chunks_per_split = (g->nchunks + ks - 1) / ks;
     g->ksplit = (g->nchunks + g->chunks_per_split - 1) / g->chunks_per_split;
@@ -158,21 +159,25 @@ double estimate_taps_us(const Plan& g, const ConvArgs& a, int ks)
     return us;
 }
 
+// The reduction is split over work-groups only when x and w are 16-byte aligned (null pointers,
+// i.e. planning without buffers, count as aligned): the workspace a descriptor needs is then the
+// need of that one plan, whatever pointers a call brings.
 bool choose_tile(const ConvArgs& a, Plan* g)
 {
     double best = 0.0;
     bool have = false;
     int bm = 0, bn = 0, bks = 1;
+    const bool may_split = is_aligned16(a.x) && is_aligned16(a.w);
     if (g->taps) {
         const int64_t tiles = (int64_t)((g->Mtot + 63) / 64) * g->groups * ((g->Kg + 63) / 64);
         if (tiles >= ((int64_t)1 << 24)) return false;
-        const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;
+        const int most = (tiles >= 2 * kCUs || !may_split) ? 1 : g->nchunks;
         int last_cps = 0;
         for (int ks = 1; ks <= most; ++ks) {
             const int cps = (g->nchunks + ks - 1) / ks;
             if (cps == last_cps) continue;
             last_cps = cps;
-            if (4.0 * ks * tiles * 4096.0 > 256e6) break;
+            if (ks > 1 && 4.0 * ks * tiles * 4096.0 > 256e6) break;   // keep the workspace modest
             const double us = estimate_taps_us(*g, a, ks);
             if (!have || us < best) {
                 have = true;
@@ -186,13 +191,13 @@ bool choose_tile(const ConvArgs& a, Plan* g)
     for (const Tile& t : kTiles) {
         const int64_t tiles = (int64_t)((g->Mtot + t.bm - 1) / t.bm) * g->groups * ((g->Kg + t.bn - 1) / t.bn);
         if (tiles >= ((int64_t)1 << 24)) continue;
-        const int most = tiles >= 2 * kCUs ? 1 : g->nchunks;      // enough tiles: no split
+        const int most = (tiles >= 2 * kCUs || !may_split) ? 1 : g->nchunks;      // enough tiles: no split
         int last_cps = 0;
         for (int ks = 1; ks <= most; ++ks) {
             const int cps = (g->nchunks + ks - 1) / ks;
             if (cps == last_cps) continue;                        // same split as the previous ks
             last_cps = cps;
-            if (4.0 * ks * tiles * t.bm * t.bn > 256e6) break;     // keep the workspace modest
+            if (ks > 1 && 4.0 * ks * tiles * t.bm * t.bn > 256e6) break;     // keep the workspace modest (none without a split)
             const double us = estimate_us(*g, a, t, ks);
             if (!have || us < best) {
                 have = true;
@@ -219,8 +224,8 @@ hipError_t launch_tile_as(const ConvArgs& a, const Plan& g, hipStream_t stream)
     const size_t lds_bytes = sizeof(float) * 2 * (size_t)(BM + BN) * WS;
     auto kern = conv_gather_kernel<BM, BN, MASK>;
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static LdsLimit granted;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
         if (e != hipSuccess) return e;
     }
     const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
@@ -233,8 +238,8 @@ hipError_t launch_tile_taps(const ConvArgs& a, const Plan& g, hipStream_t stream
     const size_t lds_bytes = sizeof(float) * NWG * 2 * (size_t)(BM + BN) * (g.kc + 2);
     auto kern = conv_taps_kernel<BM, BN, R_, S_, NWG, PACK>;
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static LdsLimit granted;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
         if (e != hipSuccess) return e;
     }
     const unsigned grid = (unsigned)(g.tiles_m * g.tiles_n * g.ksplit);
@@ -260,16 +265,10 @@ hipError_t launch_tile(const ConvArgs& a, const Plan& g, hipStream_t stream)
 
 hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stream);
 
-// What the call may need: the larger of the two kernel forms' needs, so that the figure for a
-// shape does not depend on whether the weight pointer turns out to be 16-byte aligned.
 size_t conv2d_gather_workspace_bytes(const ConvArgs& a)
 {
-    size_t need = 0;
-    for (const bool allow_taps : {true, false}) {
-        Plan g;
-        if (make_plan(a, &g, allow_taps) && choose_tile(a, &g) && plan_workspace(g) > need) need = plan_workspace(g);
-    }
-    return need;
+    Plan g;
+    return make_plan(a, &g) && choose_tile(a, &g) ? plan_workspace(g) : 0;
 }
 
 bool describe_conv2d_gather(const ConvArgs& a, ConvRoute* r)
@@ -286,11 +285,18 @@ bool describe_conv2d_gather(const ConvArgs& a, ConvRoute* r)
     return true;
 }
 
-hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken)
+hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken, int* ws_fault)
 {
     Plan g;
+    *ws_fault = 0;
     *taken = make_plan(a, &g) && choose_tile(a, &g);
     if (!*taken) return hipSuccess;
+    const size_t need = plan_workspace(g);
+    if (need > 0) {
+        if (a.ws == nullptr || a.ws_bytes < need) *ws_fault = 1;
+        else if (!is_aligned16(a.ws)) *ws_fault = 2;
+        if (*ws_fault) return hipSuccess;
+    }
     return launch_gather_plan(a, g, stream);
 }
 

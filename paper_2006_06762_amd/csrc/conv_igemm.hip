@@ -1,7 +1,5 @@
 // Variant table and shape-driven selection for the implicit-GEMM convolution
 // (kernel and its description in conv_igemm_kernel.h).
-#include <cstdlib>
-
 #include "conv_igemm_kernel.h"
 
 namespace anr {
@@ -68,43 +66,74 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
     return best;
 }
 
-}  // namespace
-
 // The tuned kernel has no split of the reduction across work-groups: with few output tiles
 // (batch 1) most CUs would idle, and the general kernel with split-K is faster.
 constexpr int kMinTunedWorkGroups = 112;
 
-// ANR_CONV_MIN_TUNED_WGS in the environment overrides the threshold (0: always the tuned kernel
-// when it can run the shape; a huge value: never).  Read at every call, so a test can switch it.
-int min_tuned_work_groups()
+struct IgemmPlan {
+    int variant;     // index into the variant table, -1: the kernel does not take the call
+    Geom g;
+    size_t lds;
+};
+
+// The one planning pass of a call: variant, geometry and LDS size, with the descriptor's route
+// applied (1: whenever a variant runs the shape; 2: never; 0: with enough output tiles).
+void plan_igemm(const ConvArgs& a, IgemmPlan* p)
 {
-    const char* e = std::getenv("ANR_CONV_MIN_TUNED_WGS");
-    if (!e || !*e) return kMinTunedWorkGroups;
-    const long v = std::strtol(e, nullptr, 10);
-    return v < 0 ? 0 : (v > (1 << 30) ? (1 << 30) : (int)v);
+    p->variant = -1;
+    if (a.route == 2) return;
+    const int best = select_variant(a, &p->g, &p->lds);
+    if (best < 0) return;
+    if (a.route != 1 && (int64_t)p->g.tiles_m * p->g.tiles_n < kMinTunedWorkGroups) return;
+    p->variant = best;
 }
+
+hipError_t launch_igemm_plan(const ConvArgs& a, const IgemmPlan& p, hipStream_t stream)
+{
+    const Geom& g = p.g;
+    const size_t lds = p.lds;
+    hipError_t err = hipSuccess;
+    switch (p.variant) {
+        case 0:
+            if (try_fixed<V224x64, 3, 64, 384>(a, g, lds, stream, &err)) return err;    // 56x56 maps, stride 1
+            return V224x64::launch(a, g, lds, stream);
+        case 1: {
+            // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
+            Geom g8;
+            size_t lds8 = 0;
+            if (V224x32c16::plan(a, &g8, &lds8) &&
+                try_fixed<V224x32c16, 6, 36, 432>(a, g8, lds8, stream, &err))
+                return err;
+        }
+            if (try_fixed<V224x32, 6, 36, 432>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 1
+            if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
+            return V224x32::launch(a, g, lds, stream);
+        case 2: return V128x64::launch(a, g, lds, stream);
+        default: return V64x64::launch(a, g, lds, stream);
+    }
+}
+
+}  // namespace
 
 bool conv2d_igemm_takes(const ConvArgs& a)
 {
-    Geom g;
-    size_t lds = 0;
-    if (select_variant(a, &g, &lds) < 0) return false;
-    return (int64_t)g.tiles_m * g.tiles_n >= min_tuned_work_groups();
+    IgemmPlan p;
+    plan_igemm(a, &p);
+    return p.variant >= 0;
 }
 
 bool describe_conv2d_igemm(const ConvArgs& a, ConvRoute* r)
 {
-    Geom g;
-    size_t lds = 0;
-    const int best = select_variant(a, &g, &lds);
-    if (best < 0 || (int64_t)g.tiles_m * g.tiles_n < min_tuned_work_groups()) return false;
+    IgemmPlan p;
+    plan_igemm(a, &p);
+    if (p.variant < 0) return false;
     static const int kTileM[4] = {224, 224, 128, 64}, kTileN[4] = {64, 32, 64, 64};
     r->kernel = 1;
-    r->tile_m = kTileM[best];
-    r->tile_n = kTileN[best];
+    r->tile_m = kTileM[p.variant];
+    r->tile_n = kTileN[p.variant];
     r->ksplit = 1;
     r->wave_groups = 1;
-    r->work_groups = g.tiles_m * g.tiles_n;
+    r->work_groups = p.g.tiles_m * p.g.tiles_n;
     r->workspace_bytes = 0;
     return true;
 }
@@ -117,30 +146,10 @@ void describe_conv2d(const ConvArgs& a, ConvRoute* r)
 
 hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
-    *taken = false;
-    Geom g;
-    size_t lds = 0;
-    const int best = select_variant(a, &g, &lds);
-    if (best < 0 || (int64_t)g.tiles_m * g.tiles_n < min_tuned_work_groups()) return hipSuccess;
-    *taken = true;
-    hipError_t err = hipSuccess;
-    switch (best) {
-        case 0:
-            if (try_fixed<V224x64, 3, 64, 384>(a, g, lds, stream, &err)) return err;    // 56x56 maps, stride 1
-            return V224x64::launch(a, g, lds, stream);
-        case 1: {
-            // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
-            Geom g8;
-            size_t lds8 = 0;
-            if (V224x32c16::plan(a, &g8, &lds8) && try_fixed<V224x32c16, 6, 36, 432>(a, g8, lds8, stream, &err))
-                return err;
-        }
-            if (try_fixed<V224x32, 6, 36, 432>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 1
-            if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
-            return V224x32::launch(a, g, lds, stream);
-        case 2: return V128x64::launch(a, g, lds, stream);
-        default: return V64x64::launch(a, g, lds, stream);
-    }
+    IgemmPlan p;
+    plan_igemm(a, &p);
+    *taken = p.variant >= 0;
+    return *taken ? launch_igemm_plan(a, p, stream) : hipSuccess;
 }
 
 size_t conv2d_workspace_bytes(const ConvArgs& a)
@@ -148,12 +157,13 @@ size_t conv2d_workspace_bytes(const ConvArgs& a)
     return conv2d_igemm_takes(a) ? 0 : conv2d_gather_workspace_bytes(a);
 }
 
-hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream)
+hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault)
 {
+    *ws_fault = 0;
     bool taken = false;
     hipError_t err = launch_conv2d_igemm(a, stream, &taken);
     if (taken || err != hipSuccess) return err;
-    err = launch_conv2d_gather(a, stream, &taken);
+    err = launch_conv2d_gather(a, stream, &taken, ws_fault);
     if (taken || err != hipSuccess) return err;
     return launch_conv2d_direct(a, stream);
 }

@@ -74,28 +74,8 @@ struct Geom {
     int tiles_m, tiles_n, xcd_m, xcd_n;
     uint32_t x_bytes, w_bytes;   // extents of the x view and of w, for the buffer descriptors
     FastDiv d_sub_n;            // divisor tiles_n / xcd_n
-#ifdef ANR_IGEMM_TRACE
-    long long* trace;   // experiment harness only: per-work-group phase timestamps
-#endif
 };
 
-#ifdef ANR_IGEMM_TRACE
-#define ANR_TRACE(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
-#define ANR_TRACE_END(slot) do { __builtin_amdgcn_s_waitcnt(0); ANR_TRACE(slot); } while (0)
-#define ANR_TRACE_CLK(slot) do { if (threadIdx.x == 0 && g.trace) g.trace[blockIdx.x * 8 + (slot)] = clock64(); } while (0)
-#define ANR_PHASE_DECL long long ph_t = 0, ph_acc[4] = {0, 0, 0, 0}
-#define ANR_PHASE_START do { ph_t = clock64(); } while (0)
-#define ANR_PHASE(k) do { long long now_ = clock64(); ph_acc[k] += now_ - ph_t; ph_t = now_; } while (0)
-#define ANR_PHASE_FLUSH do { if ((threadIdx.x & 63) == 0 && g.trace) { long long* d_ = g.trace + (long long)gridDim.x * 8 + (blockIdx.x * 16 + (threadIdx.x >> 6)) * 4; for (int k_ = 0; k_ < 4; ++k_) d_[k_] = ph_acc[k_]; } } while (0)
-#else
-#define ANR_PHASE_DECL
-#define ANR_PHASE_START do { } while (0)
-#define ANR_PHASE(k) do { } while (0)
-#define ANR_PHASE_FLUSH do { } while (0)
-#define ANR_TRACE_CLK(slot) do { } while (0)
-#define ANR_TRACE(slot) do { } while (0)
-#define ANR_TRACE_END(slot) do { } while (0)
-#endif
 
 constexpr int kMaxUnits = 8;
 
@@ -131,7 +111,6 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     const int patch_sz = CK * P;                     // floats per patch buffer
     constexpr int WTS_SZ = BN * WS;                  // floats per weight buffer
 
-    ANR_TRACE(0);
     extern __shared__ __attribute__((aligned(16))) float smem[];
     // layout: patch[2][patch_sz], then wts[2][WTS_SZ]
     char* const lds = reinterpret_cast<char*>(smem);
@@ -249,7 +228,6 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         }
     };
 
-    ANR_TRACE(1);
 #pragma unroll
     for (int j = 0; j < NSIDE; ++j) side_load(j, 0u, 0u);
     for (int idx = tid; idx < (2 * patch_sz) / 4; idx += NT)
@@ -258,10 +236,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
 #pragma unroll
     for (int j = 0; j < NSIDE; ++j) side_store(j, 0, 0);
     __syncthreads();
-    ANR_TRACE(2);
-    ANR_TRACE_CLK(6);
 
-    ANR_PHASE_DECL;
     // One chunk: MFMAs on LDS buffer `buf`, staging of chunk cc+1 into the other buffer.
     auto chunk = [&](int cc, auto buf_c) {
         constexpr int buf = decltype(buf_c)::value;
@@ -282,12 +257,9 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             for (int nb = 0; nb < WN_BLK; ++nb)
                 b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + rd_b);
         };
-        ANR_PHASE_START;
         read_step(0, a_cur, b_cur);
 #pragma unroll
         for (int t = 0; t < SPW; ++t) {
-            if (t == 1) ANR_PHASE(0);
-            if (t == SPW - 1) ANR_PHASE(1);
             // reads of step t+1 are issued before the MFMAs of step t: their latency hides
             // behind those MFMAs instead of stalling the next ones
             if (t + 1 < SPW) read_step(t + 1, a_nxt, b_nxt);
@@ -307,18 +279,13 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
 #pragma unroll
             for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
         }
-        ANR_PHASE(2);
         __syncthreads();
-        ANR_PHASE(3);
     };
     for (int cc = 0; cc < nchunks; cc += 2) {
         chunk(cc, std::integral_constant<int, 0>{});
         if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
     }
 
-    ANR_PHASE_FLUSH;
-    ANR_TRACE(3);
-    ANR_TRACE_CLK(7);
     // ---- reduce-scatter of the k-split partial accumulators: block b belongs to wave ks == b % KSPLIT
     //      of its tile; the others leave their partials in LDS (the staging buffers are free now)
     if (KSPLIT > 1) {
@@ -351,7 +318,6 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             }
         }
     }
-    ANR_TRACE(4);
 
     // ---- epilogue, per owned block: accumulator register r of lane (h, r32) is pixel
     //      8*(r/4) + 4*h + r%4, channel r32 of the 32x32 block: four consecutive pixels per quad
@@ -393,15 +359,24 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             }
         }
     }
-    ANR_TRACE_END(5);
 }
 
-// Largest number of virtual rows any M-tile of BM pixels needs.
+// Largest number of virtual rows any M-tile of BM pixels needs.  What a whole tile needs
+// depends only on where in an image it starts, m0 mod OH*OW, and that repeats after
+// OH*OW / gcd(BM, OH*OW) tiles; the clipped last tile needs no more than a whole one at the
+// same start.  So one period is scanned, not every tile of a large batch.
 inline int max_virtual_rows(const ConvArgs& a, int BM, int HV)
 {
     const int64_t Mtot = (int64_t)a.N * a.OH * a.OW;
+    const int64_t ohow = (int64_t)a.OH * a.OW;
+    int64_t x = BM, y = ohow;
+    while (y) { const int64_t t = x % y; x = y; y = t; }
+    const int64_t period = ohow / x;                      // tiles until the start offset repeats
+    const int64_t tiles = (Mtot + BM - 1) / BM;
+    const int64_t scan = tiles < period ? tiles : period;
     int vr = 0;
-    for (int64_t m0 = 0; m0 < Mtot; m0 += BM) {
+    for (int64_t t = 0; t < scan; ++t) {
+        const int64_t m0 = t * BM;
         const int64_t m1 = (m0 + BM < Mtot ? m0 + BM : Mtot) - 1;
         const int64_t g0 = m0 / a.OW, g1 = m1 / a.OW;
         const int64_t va = (g0 / a.OH) * HV + (g0 % a.OH) * a.stride_h;
@@ -487,8 +462,8 @@ struct Variant {
     {
         auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T>;
         if (lds_bytes > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            static LdsLimit granted;
+            hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
             if (e != hipSuccess) return e;
         }
         dim3 grid((unsigned)(g.tiles_m * g.tiles_n));

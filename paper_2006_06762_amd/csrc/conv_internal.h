@@ -8,7 +8,8 @@ hipError_t launch_conv2d_direct(const ConvArgs& a, hipStream_t stream);
 hipError_t launch_dwconv_direct(const ConvArgs& a, hipStream_t stream);
 
 // Implicit-GEMM MFMA convolution.  Returns false in *taken when the geometry is
-// outside what the kernel supports (the caller then uses the direct kernel).
+// outside what the kernel supports or the route rules it out (the caller then uses the
+// general kernel).
 hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* taken);
 
 // Whether launch_conv2d_igemm would take the problem (same selection, nothing launched).
@@ -16,7 +17,8 @@ bool conv2d_igemm_takes(const ConvArgs& a);
 
 // General implicit-GEMM convolution with gathered operands and optional split-K over a
 // workspace.  *taken false: extents beyond its 32-bit offsets (the direct kernel runs then).
-hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken);
+// *ws_fault as in launch_conv2d.
+hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken, int* ws_fault);
 size_t conv2d_gather_workspace_bytes(const ConvArgs& a);
 
 // What a launch would do, for introspection (nothing is launched).

@@ -278,14 +278,6 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* out, int64_t r
 // stage put four waves on every SIMD, so one wave's staging overlaps another's MFMAs and each
 // wave issues 8 loads instead of 32: 6.5 -> 5.8 us cold.  Weaving the later stages' loads
 // between the MFMAs of the four-stage form had changed nothing.
-#ifdef ANR_GEMM_TRACE
-__device__ long long* anr_gemm_trace = nullptr;
-#define GT(slot) do { if (threadIdx.x == 0 && anr_gemm_trace) anr_gemm_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
-#define GT_END(slot) do { __builtin_amdgcn_s_waitcnt(0); GT(slot); } while (0)
-#else
-#define GT(slot) do { } while (0)
-#define GT_END(slot) do { } while (0)
-#endif
 
 constexpr int kKsLd = 36;                       // LDS row stride (floats) of a 32-wide stage
 constexpr int kKsStage = 2 * 32 * kKsLd;        // floats per stage: A block then B block
@@ -296,7 +288,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile32_ksplit_kernel(const GemmA
 {
     static_assert(16 % NW == 0, "a wave finishes 16 / NW accumulator registers");
     extern __shared__ __attribute__((aligned(16))) float lds[];   // [NW waves][NST][kKsStage]
-    GT(0);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -335,7 +326,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile32_ksplit_kernel(const GemmA
     // keep every load above the first use (the scheduler would otherwise sink each load to
     // its use to save registers, and the wave would see one memory latency per stage)
     __builtin_amdgcn_sched_barrier(0);
-    GT(1);
 
     f32x16 acc, acc2;
 #pragma unroll
@@ -368,13 +358,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile32_ksplit_kernel(const GemmA
         }
     }
 
-    GT(2);
     __syncthreads();            // every wave is done with its staging region: reuse it
     float* red = lds;
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r] + acc2[r];
     __syncthreads();
-    GT(3);
     // wave w finishes accumulator registers (16 / NW) w ...: register r is row 8 (r / 4) + 4 h + r % 4
 #pragma unroll
     for (int q = 0; q < 16 / NW; ++q) {
@@ -384,7 +372,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_tile32_ksplit_kernel(const GemmA
         for (int o = 0; o < NW; ++o) v += red[(o * 16 + r) * 64 + lane];
         C[(int64_t)(tm * 32 + 8 * (r / 4) + 4 * h + (r % 4)) * p.ldc + tn * 32 + r32] = v;
     }
-    GT_END(4);
 }
 
 template <int NST, int NW>
@@ -394,8 +381,8 @@ hipError_t launch_ksplit(const GemmArgs& a, hipStream_t stream)
     const size_t lds_bytes = sizeof(float) * NW * NST * kKsStage;
     auto kern = gemm_tile32_ksplit_kernel<NST, NW>;
     if (lds_bytes > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static LdsLimit granted;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
         if (e != hipSuccess) return e;
     }
     const int xcd_map = (tiles_m % 4 == 0) && (tiles_n % 2 == 0);
@@ -418,8 +405,8 @@ hipError_t launch_pipe(const GemmArgs& a, hipStream_t stream)
     const size_t lds_bytes = NWG * gpipe::Tiles<BM, BN, NT>::lds_bytes;
     auto kern = gpipe::gemm_pipe_kernel<BM, BN, NT, NWG>;
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static LdsLimit granted;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
         if (e != hipSuccess) return e;
     }
     return launch_kernel(kern, dim3((unsigned)(tiles_m * tiles_n), 1, a.batch), dim3(256 * NWG), lds_bytes, stream, a,

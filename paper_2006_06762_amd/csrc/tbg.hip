@@ -29,8 +29,8 @@ hipError_t launch_tbs_rows32(const tbg::Args& t0, int batch, int vec_store, hipS
     constexpr int UTW = (T::rows_q + T::rows_k) / 16;
     auto kern = whole ? tbg::tbs_rows32_kernel<UTW, true, KB, true> : tbg::tbs_rows32_kernel<UT, true, KB, false>;
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static LdsLimit granted[2];    // one per kernel form
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted[whole ? 1 : 0]);
         if (e != hipSuccess) return e;
     }
     return launch_kernel(kern, dim3((unsigned)items), dim3(256), lds_bytes, stream, t, ld, vec_store);

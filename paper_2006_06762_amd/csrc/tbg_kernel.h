@@ -45,18 +45,9 @@ struct Args {
     FastDiv d_tiles_j, d_tiles_i, d_h;   // divisors tiles_j, tiles_i, H (tbg_tile64_kernel)
 };
 
-#ifdef ANR_TBG_TRACE
-__device__ long long* anr_tbg_trace = nullptr;
-#define TT(slot) do { if (threadIdx.x == 0 && anr_tbg_trace) anr_tbg_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
-#define TT_END(slot) do { __builtin_amdgcn_s_waitcnt(0); TT(slot); } while (0)
-#else
-#define TT(slot) do { } while (0)
-#define TT_END(slot) do { } while (0)
-#endif
 
 __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
 {
-    TT(0);
     __shared__ __attribute__((aligned(16))) float qs[kTile * kLds];
     __shared__ __attribute__((aligned(16))) float ks[kTile * kLds];
 
@@ -98,7 +89,6 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             rq[u] = ldg4(qb + ri * p.qs_s + dd);
             rk[u] = ldg4(kb + rj * p.ks_s + dd);
         }
-        TT(1);
         if (d0 > 0) __syncthreads();             // previous chunk fully consumed
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -106,7 +96,6 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             *reinterpret_cast<f32x4*>(&ks[(srow + 16 * u) * kLds + sd]) = din ? rk[u] : zero4();
         }
         __syncthreads();
-        TT(2);
 
         f32x4 a[8], bb[8];
 #pragma unroll
@@ -124,7 +113,6 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
-    TT(3);
 
     // register r of lane (h2, r32): row 8*(r/4) + 4*h2 + r%4, column r32 of the block
     float* __restrict__ ob = p.out + b * p.os_b + hh * p.os_h;
@@ -136,7 +124,6 @@ __global__ __launch_bounds__(256) void tbg_tile_kernel(const Args p)
             if (row < p.S) ob[row * p.os_i + col] = acc[r];
         }
     }
-    TT_END(4);
 }
 
 // The same tile for whole tiles and whole chunks (S and D multiples of 64: every shape of the

@@ -49,7 +49,7 @@ int main(void) {
          offsetof(anr_conv_desc, x_stride), offsetof(anr_conv_desc, y_stride));
   printf("%zu %zu %zu\n", offsetof(anr_tbg_desc, q_stride), offsetof(anr_tbg_desc, k_stride),
          offsetof(anr_tbg_desc, o_stride));
-  printf("%zu %zu\n", offsetof(anr_conv_desc, groups), offsetof(anr_conv_desc, reserved));
+  printf("%zu %zu\n", offsetof(anr_conv_desc, groups), offsetof(anr_conv_desc, route));
   return 0; }''')
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
@@ -58,7 +58,7 @@ int main(void) {
     exp = [ctypes.sizeof(B.GemmDesc), ctypes.sizeof(B.ConvDesc), ctypes.sizeof(B.TbgDesc),
            B.GemmDesc.strideC.offset, B.ConvDesc.layout.offset, B.ConvDesc.x_stride.offset,
            B.ConvDesc.y_stride.offset, B.TbgDesc.q_stride.offset, B.TbgDesc.k_stride.offset,
-           B.TbgDesc.o_stride.offset, B.ConvDesc.groups.offset, B.ConvDesc.reserved.offset]
+           B.TbgDesc.o_stride.offset, B.ConvDesc.groups.offset, B.ConvDesc.route.offset]
     assert got == exp
 
 
@@ -79,6 +79,9 @@ def test_gemm_validation():
     assert gemm_status(ldc=3) == B.ANR_ERR_INVALID_ARG
     assert gemm_status(batch=2, strideC=15) == B.ANR_ERR_INVALID_ARG     # overlapping outputs
     assert gemm_status(batch=70000, strideC=16) == B.ANR_ERR_UNSUPPORTED
+    # extents and leading dimensions whose products would leave 64 bits are refused, not multiplied
+    assert gemm_status(M=1 << 30, lda=4) == B.ANR_ERR_UNSUPPORTED
+    assert gemm_status(ldc=1 << 62, batch=2, strideC=1 << 62) == B.ANR_ERR_UNSUPPORTED
     d = B.GemmDesc(4, 4, 4, 4, 4, 4, 1, 0, 0, 0)
     lib = B.raw()
     assert lib.anr_gemm(None, DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_NULL
@@ -111,7 +114,8 @@ def test_conv_validation(fn):
     assert conv_status(fn, dil_w=0) == B.ANR_ERR_INVALID_ARG
     assert conv_status(fn, H=4, R=3, dil_h=2, pad_h=0) == B.ANR_ERR_INVALID_ARG   # dilated kernel taller than the image
     assert conv_status(fn, groups=-1) == B.ANR_ERR_INVALID_ARG
-    assert conv_status(fn, reserved=1) == B.ANR_ERR_INVALID_ARG
+    assert conv_status(fn, route=3) == B.ANR_ERR_INVALID_ARG
+    assert conv_status(fn, route=-1) == B.ANR_ERR_INVALID_ARG
     if fn != "anr_dwconv":
         assert conv_status(fn, groups=3) == B.ANR_ERR_INVALID_ARG                 # channels not a multiple
     assert conv_status(fn, layout=1) == B.ANR_ERR_UNSUPPORTED
@@ -156,6 +160,10 @@ def test_tbg_validation(fn):
     d = B.TbgDesc(1, 4, 2, 4)
     d.o_stride = (ctypes.c_int64 * 4)(32, 16, 3, 1)       # rows overlap
     assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+    d.o_stride = (ctypes.c_int64 * 4)(32, 15, 4, 1)       # heads overlap
+    assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+    d.o_stride = (ctypes.c_int64 * 4)(31, 16, 4, 1)       # batches overlap
+    assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
     if fn == "anr_tbs":
         d = B.TbgDesc(1, 2048, 1, 4)
         assert f(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
@@ -172,6 +180,8 @@ def test_nrm_validation():
     assert lib.anr_nrm(ctypes.byref(d), None, DUMMY, None, 0, None) == B.ANR_ERR_NULL
     assert lib.anr_nrm(ctypes.byref(d), DUMMY, None, None, 0, None) == B.ANR_ERR_NULL
     assert lib.anr_nrm(ctypes.byref(B.NrmDesc(8, 8, 8, 70000, 64)), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
+    assert lib.anr_nrm(ctypes.byref(B.NrmDesc(8, 8, 8, 2, 63)), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG  # matrices overlap
+    assert lib.anr_nrm(ctypes.byref(B.NrmDesc(8, 8, 1 << 40, 1, 0)), DUMMY, DUMMY, None, 0, None) == B.ANR_ERR_UNSUPPORTED
     assert B.workspace_size(B.ANR_OP_NRM, d) == 0                      # one slice: no partial sums
     big = B.NrmDesc(4096, 4096, 4096, 1, 0)
     need = B.workspace_size(B.ANR_OP_NRM, big)
@@ -218,10 +228,43 @@ def test_conv_route_benchmark_configs_take_the_patch_kernel():
         d, r = route(shape, K, 3, stride, 1)
         assert r.kernel == B.ANR_CONV_KERNEL_PATCH and (r.tile_m, r.tile_n) == tile
         assert r.ksplit == 1 and r.workspace_bytes == 0 and r.work_groups == 224
-    # anr_workspace_size is the bound for any pointer alignment: the stride-2 layer would split its
-    # reduction in the general kernel if x or w were not 16-byte aligned
-    assert B.workspace_size(B.ANR_OP_CONV2D, B.conv_desc((16, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1))) == 0
-    assert B.workspace_size(B.ANR_OP_CONV2D, B.conv_desc((16, 256, 28, 28), 512, 3, 3, (2, 2), (1, 1))) > 0
+        assert B.workspace_size(B.ANR_OP_CONV2D, d) == 0 and B.workspace_size(B.ANR_OP_CONV_BN_RELU, d) == 0
+
+
+def test_conv_route_follows_the_descriptor_field():
+    # many output tiles: the library's choice is the patch kernel; route 2 keeps it out
+    auto = B.conv_desc((16, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1))
+    gen = B.conv_desc((16, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1), route=B.ANR_CONV_ROUTE_GENERAL)
+    assert B.conv2d_route(auto).kernel == B.ANR_CONV_KERNEL_PATCH
+    assert B.conv2d_route(gen).kernel == B.ANR_CONV_KERNEL_TAPS
+    # few output tiles: the library's choice is the general kernel with a split reduction; route 1
+    # forces the patch kernel, which needs no workspace
+    auto = B.conv_desc((1, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1))
+    patch = B.conv_desc((1, 64, 56, 56), 64, 3, 3, (1, 1), (1, 1), route=B.ANR_CONV_ROUTE_PATCH)
+    ra, rp = B.conv2d_route(auto), B.conv2d_route(patch)
+    assert ra.kernel == B.ANR_CONV_KERNEL_TAPS and ra.ksplit > 1
+    assert rp.kernel == B.ANR_CONV_KERNEL_PATCH and rp.workspace_bytes == 0
+    # the workspace figure is the plan's own need, route by route
+    assert B.workspace_size(B.ANR_OP_CONV2D, auto) == ra.workspace_bytes > 0
+    assert B.workspace_size(B.ANR_OP_CONV2D, patch) == 0
+    # a shape the patch kernel cannot run (width not a multiple of 4) takes the general one under any route
+    odd = B.conv_desc((16, 64, 14, 14), 64, 3, 3, (1, 1), (1, 1), route=B.ANR_CONV_ROUTE_PATCH)
+    assert B.conv2d_route(odd).kernel == B.ANR_CONV_KERNEL_TAPS
+
+
+def test_no_environment_variable_steers_the_library():
+    # what a call does follows from its arguments alone
+    csrc = os.path.join(ROOT, "paper_2006_06762_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        assert "getenv" not in text and "environ" not in text, name
+
+
+def test_conv_route_large_batch_without_split_keeps_the_mfma_kernels():
+    # a VGG-style stem at batch 32: 3 channels rule out the tap kernels, and the cap on the split-K
+    # workspace must not apply to plans that do not split
+    d, r = route((32, 3, 224, 224), 64, 3, 1, 1)
+    assert r.kernel == B.ANR_CONV_KERNEL_GATHER and r.ksplit == 1 and r.workspace_bytes == 0
 
 
 def test_conv_route_by_kernel_size_and_channels():
@@ -229,13 +272,13 @@ def test_conv_route_by_kernel_size_and_channels():
     # few output tiles: the tuned kernel steps aside, the reduction is split through the workspace
     d, r = route((1, 64, 56, 56), 64, 3, 1, 1)
     assert r.kernel == K.ANR_CONV_KERNEL_TAPS and r.ksplit > 1 and r.workspace_bytes > 0
-    assert r.workspace_bytes <= K.workspace_size(K.ANR_OP_CONV2D, d)
+    assert r.workspace_bytes == K.workspace_size(K.ANR_OP_CONV2D, d)
     # 14x14 and 7x7 maps (width not a multiple of 4), pointwise layers: compile-time taps, 64x64 tiles
     for shape, Kout, R, pad in [((16, 256, 14, 14), 256, 3, 1), ((16, 512, 7, 7), 512, 3, 1), ((16, 64, 56, 56), 64, 1, 0),
                                 ((16, 1024, 14, 14), 256, 1, 0)]:
         d, r = route(shape, Kout, R, 1, pad)
         assert r.kernel == K.ANR_CONV_KERNEL_TAPS and (r.tile_m, r.tile_n) == (64, 64)
-        assert r.workspace_bytes <= K.workspace_size(K.ANR_OP_CONV2D, d)
+        assert r.workspace_bytes == K.workspace_size(K.ANR_OP_CONV2D, d)
     # 7x7 stem and 5x5: one channel per chunk
     assert route((16, 3, 224, 224), 64, 7, 2, 3)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
     assert route((2, 32, 28, 28), 64, 5, 1, 2)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
@@ -262,7 +305,7 @@ def test_conv_route_wave_groups_and_split():
                                 ((1, 3, 224, 224), 64, 7, 3)]:
         d, r = route(shape, Kout, R, 1 if R == 3 else 2, pad)
         assert 1 <= r.ksplit <= 4608 and r.work_groups % r.ksplit == 0
-        assert r.workspace_bytes <= B.workspace_size(B.ANR_OP_CONV2D, d)
+        assert r.workspace_bytes == B.workspace_size(B.ANR_OP_CONV2D, d)
         assert (r.workspace_bytes > 0) == (r.ksplit > 1)
 
 

@@ -202,12 +202,11 @@ CONV_GENERIC = [
 
 
 @pytest.fixture(params=["tuned", "general"])
-def conv_route(request, monkeypatch):
+def conv_route(request):
     """Runs a test once with the tuned patch-staging kernel wherever it can take the shape
-    and once with the general gather kernel for everything (the library reads the variable
-    at every call; by default the choice depends on the number of output tiles)."""
-    monkeypatch.setenv("ANR_CONV_MIN_TUNED_WGS", "0" if request.param == "tuned" else "1000000000")
-    return request.param
+    and once with the general gather kernel for everything: the value for the descriptor's
+    `route` field (left at 0, the choice depends on the number of output tiles)."""
+    return 1 if request.param == "tuned" else 2
 
 
 @pytest.mark.parametrize("shape", CONV_FAST + CONV_GENERIC, ids=str)
@@ -215,7 +214,7 @@ def conv_route(request, monkeypatch):
 def test_conv2d_small(anr, conv_route, shape, ints):
     x, w = I.conv_inputs(shape, 200, ints=ints)
     buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
-    anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad)
+    anr.conv2d(dev(x), dev(w), y, shape.stride, shape.pad, route=conv_route)
     check_guard(buf)
     assert_parity(y, oracle.conv2d(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
 
@@ -359,7 +358,7 @@ def test_conv2d_configs(anr, conv_route, name):
     cfg = I.config_inputs(name)
     s = cfg["shape"]
     buf, y = guarded((s.N, s.K, s.OH, s.OW))
-    anr.conv2d(dev(cfg["x"]), dev(cfg["w"]), y, s.stride, s.pad)
+    anr.conv2d(dev(cfg["x"]), dev(cfg["w"]), y, s.stride, s.pad, route=conv_route)
     check_guard(buf)
     assert_parity(y, oracle.conv2d(cfg["x"], cfg["w"], s.stride, s.pad), what=name)
 
@@ -381,7 +380,7 @@ def test_conv2d_delta_kernel_is_shift(anr, conv_route):
         for c in range(C):
             w[c, c, r0, s0] = 1.0
         y = torch.empty((2, C, H, W), device="cuda")
-        anr.conv2d(dev(x), dev(w), y, (1, 1), (1, 1))
+        anr.conv2d(dev(x), dev(w), y, (1, 1), (1, 1), route=conv_route)
         exp = np.zeros((2, C, H, W), np.float32)
         for oh in range(H):
             for ow in range(W):
@@ -398,7 +397,7 @@ def test_conv2d_strided_views(anr, conv_route):
     xw = torch.zeros((2, 10, 14, 24), device="cuda")
     xw[:, 1:9, 1:13, 4:20] = dev(x)
     yw = torch.full((2, 18, 13, 20), CANARY, device="cuda")
-    anr.conv2d(xw[:, 1:9, 1:13, 4:20], dev(w), yw[:, 1:17, 0:12, 4:20], s.stride, s.pad)
+    anr.conv2d(xw[:, 1:9, 1:13, 4:20], dev(w), yw[:, 1:17, 0:12, 4:20], s.stride, s.pad, route=conv_route)
     ref = oracle.conv2d(x, w, s.stride, s.pad)
     assert_parity(yw[:, 1:17, 0:12, 4:20].contiguous(), ref, what="strided conv (aligned)")
     assert float((yw == CANARY).sum()) == yw.numel() - ref.size
@@ -437,7 +436,7 @@ def test_conv_bn_relu_small(anr, conv_route, shape):
     gamma, beta, mean, var = I.bn_inputs(shape.K, 301)
     buf, y = guarded((shape.N, shape.K, shape.OH, shape.OW))
     anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y,
-                     shape.stride, shape.pad)
+                     shape.stride, shape.pad, route=conv_route)
     check_guard(buf)
     ref = oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, shape.stride, shape.pad)
     assert_parity(y, ref, what=str(shape))
@@ -787,10 +786,9 @@ def test_conv_bn_relu_stem_split_k(anr):
     assert_parity(y, ref, what="7x7 ConvLayer")
 
 
-def test_conv2d_random_geometries_tuned_kernel(anr, monkeypatch):
+def test_conv2d_random_geometries_tuned_kernel(anr):
     """Seeded random geometries inside what the tuned patch-staging kernel takes (3x3 with C % 8 == 0,
     1x1 with C % 32 == 0 and C >= 256, W % 4 == 0), forced onto it whatever the tile count."""
-    monkeypatch.setenv("ANR_CONV_MIN_TUNED_WGS", "0")
     g = np.random.Generator(np.random.PCG64(980))
     for i in range(40):
         if g.random() < 0.75:
@@ -805,7 +803,7 @@ def test_conv2d_random_geometries_tuned_kernel(anr, monkeypatch):
             continue
         x, w = I.conv_inputs(s, 981 + i, ints=True)
         buf, y = guarded((s.N, s.K, s.OH, s.OW))
-        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+        anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, route=1)
         check_guard(buf)
         assert_parity(y, oracle.conv2d(x, w, s.stride, s.pad), exact=True, what="random tuned conv %d %s" % (i, s))
 
