@@ -153,6 +153,25 @@ anr_status anr_gemm(const anr_gemm_desc *desc, const float *A, const float *B, f
 anr_status anr_conv2d(const anr_conv_desc *desc, const float *x, const float *w, float *y,
                       void *ws, size_t ws_bytes, void *hip_stream);
 
+/* anr_conv2d for callers that cannot allocate device memory, and so cannot bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as anr_conv2d (bit for bit), but the
+ * partial tiles of a split reduction go to a fixed array of
+ * ANR_STATIC_SCRATCH_BYTES that the library holds in the memory of every GPU it is
+ * loaded on, from load time until the process ends.  The call allocates and frees
+ * nothing and synchronises nothing.  A descriptor whose plan needs more
+ * (anr_workspace_size(ANR_OP_CONV2D, desc) > ANR_STATIC_SCRATCH_BYTES) returns
+ * ANR_ERR_WORKSPACE before anything is launched; the limit covers every layer of the
+ * paper's shape lists at batch 1 and 16.  All calls on one GPU share that GPU's
+ * array: calls that need it and may overlap in time (different streams, different
+ * threads) race on it, so keep them on one stream or order them yourself; its
+ * contents need not be cleared between calls (every partial tile is written before
+ * it is read).  The first call on a device that needs the array looks its address
+ * up in the runtime once; make that call outside a graph capture. */
+#define ANR_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+anr_status anr_conv2d_noalloc(const anr_conv_desc *desc, const float *x, const float *w, float *y,
+                              void *hip_stream);
+
 /* ConvLayer (Sec. 7.2): the convolution above, then inference batch
  * normalisation per output channel, gamma*(v-mean)/sqrt(var+eps)+beta, then
  * ReLU, in one kernel (Table 1 rule 4: element-wise consumers are fused into

@@ -27,7 +27,7 @@ ANR_OK, ANR_ERR_NULL, ANR_ERR_INVALID_ARG, ANR_ERR_UNSUPPORTED, ANR_ERR_WORKSPAC
 ANR_LAYOUT_NCHW = 0
 ANR_OP_GEMM, ANR_OP_CONV2D, ANR_OP_CONV_BN_RELU, ANR_OP_DWCONV, ANR_OP_TBG, ANR_OP_TBS, ANR_OP_NRM = range(7)
 
-EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
+EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
            "anr_workspace_size", "anr_conv2d_route", "anr_status_string", "anr_version", "anr_last_hip_error",
            "anr_last_hip_error_string")
 
@@ -75,6 +75,7 @@ class TbgDesc(ctypes.Structure):
 _vp = ctypes.c_void_p
 _lib.anr_gemm.argtypes = [ctypes.POINTER(GemmDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_conv2d.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.anr_conv2d_noalloc.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp]
 _lib.anr_conv_bn_relu.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float,
                                   _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_dwconv.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -83,7 +84,7 @@ _lib.anr_tbs.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_s
 _lib.anr_nrm.argtypes = [ctypes.POINTER(NrmDesc), _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_workspace_size.argtypes = [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_size_t)]
 _lib.anr_conv2d_route.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ConvRoute)]
-for _name in ("anr_gemm", "anr_conv2d", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
+for _name in ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
               "anr_workspace_size"):
     getattr(_lib, _name).restype = ctypes.c_int
 _lib.anr_status_string.argtypes = [ctypes.c_int]
@@ -219,6 +220,20 @@ def conv2d(x, w, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1, ro
                   route=route)
     wp, wb = _workspace(ANR_OP_CONV2D, d, ws)
     _check(_lib.anr_conv2d(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), wp, wb, _stream()), "anr_conv2d")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def conv2d_noalloc(x, w, y, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, route=ANR_CONV_ROUTE_AUTO):
+    """conv2d without a workspace argument: split reductions use the library's static scratch array."""
+    K, _, R, S = w.shape
+    if not w.is_contiguous():
+        raise ValueError("weights must be packed")
+    d = conv_desc(tuple(x.shape), K, R, S, stride, pad, _conv_strides(x), _conv_strides(y), dil=dil, groups=groups,
+                  route=route)
+    _check(_lib.anr_conv2d_noalloc(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _stream()), "anr_conv2d_noalloc")
     return y
 
 

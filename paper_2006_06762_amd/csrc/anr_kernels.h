@@ -101,6 +101,11 @@ size_t conv2d_workspace_bytes(const ConvArgs& a);
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault);
 hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
 
+// The library's static scratch array (static_scratch.hip): device address of the current
+// device's copy and its size.  Allocates nothing.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+hipError_t static_scratch(void** ptr, size_t* bytes);
+
 // out[b] = sqrt(sum of squares of the N x M matrix b); rows `ld` apart, matrices `stride` apart.
 struct NrmArgs {
     const float* x;

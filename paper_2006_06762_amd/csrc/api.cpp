@@ -235,6 +235,22 @@ anr_status anr_conv2d(const anr_conv_desc* d, const float* x, const float* w, fl
     return run_conv2d(&a, ws, ws_bytes, hip_stream);
 }
 
+anr_status anr_conv2d_noalloc(const anr_conv_desc* d, const float* x, const float* w, float* y, void* hip_stream)
+{
+    ConvGeom g;
+    anr_status st = check_conv(d, false, &g);
+    if (st != ANR_OK) return st;
+    if (!x || !w || !y) return ANR_ERR_NULL;
+    anr::ConvArgs a = make_conv_args(d, g, x, w, y);
+    // plans that need no workspace never touch the array (nor the runtime, to look it up)
+    if (anr::conv2d_workspace_bytes(a) == 0) return run_conv2d(&a, nullptr, 0, hip_stream);
+    void* scratch = nullptr;
+    size_t scratch_bytes = 0;
+    const hipError_t e = anr::static_scratch(&scratch, &scratch_bytes);
+    if (e != hipSuccess) return launch_status(e);
+    return run_conv2d(&a, scratch, scratch_bytes, hip_stream);
+}
+
 anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float* w, const float* gamma,
                             const float* beta, const float* mean, const float* var, float eps, float* y,
                             void* ws, size_t ws_bytes, void* hip_stream)

@@ -143,6 +143,19 @@ def test_conv_null_pointers():
                                 ctypes.c_float(float("nan")), DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
 
 
+def test_conv2d_noalloc_validation():
+    # the entry point without a workspace argument validates as anr_conv2d does, before anything else
+    lib = B.raw()
+    d = B.conv_desc((1, 4, 8, 8), 4, 3, 3, (1, 1), (1, 1))
+    assert lib.anr_conv2d_noalloc(None, DUMMY, DUMMY, DUMMY, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d_noalloc(ctypes.byref(d), None, DUMMY, DUMMY, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d_noalloc(ctypes.byref(d), DUMMY, DUMMY, None, None) == B.ANR_ERR_NULL
+    d.stride_w = 0
+    assert lib.anr_conv2d_noalloc(ctypes.byref(d), DUMMY, DUMMY, DUMMY, None) == B.ANR_ERR_INVALID_ARG
+    text = open(HEADER).read()
+    assert int(re.search(r"ANR_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", text).group(1)) << 20 == B.STATIC_SCRATCH_BYTES
+
+
 @pytest.mark.parametrize("fn", ["anr_tbg", "anr_tbs"])
 def test_tbg_validation(fn):
     lib = B.raw()
