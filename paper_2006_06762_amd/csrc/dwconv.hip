@@ -34,6 +34,46 @@ hipError_t launch_rows_s2(const ConvArgs& a, hipStream_t stream)
                          a, lpr, ppw, planes, row_chunks, dv);
 }
 
+// Stride 1 on dense tensors: see dwconv3x3_stream_kernel.  NI rounds of RPR rows hold an item's
+// input rows: a whole plane if it fits, else equal runs of rows with their two halo rows.
+template <int W4_T, int NI>
+hipError_t launch_stream_as(const ConvArgs& a, hipStream_t stream)
+{
+    dw::StreamGeom g{};
+    g.W4 = a.W / 4;
+    g.RPR = 64 / g.W4;
+    g.LPR = g.RPR * g.W4;
+    const int rows_in = NI * g.RPR;
+    int rc = a.H;
+    if (rows_in < a.H) {
+        rc = rows_in - 2;
+        const int chunks = (a.H + rc - 1) / rc;
+        rc = (a.H + chunks - 1) / chunks;
+    }
+    g.RC = rc;
+    g.chunks = (a.H + rc - 1) / rc;
+    g.hw = a.H * a.W;
+    g.slice = ((rc + 2) * a.W + 8 + 3) / 4 * 4;
+    g.items = a.N * a.C * g.chunks;
+    g.d_chunks = make_fastdiv(g.chunks);
+    g.d_w4 = make_fastdiv(g.W4);
+    g.d_c = make_fastdiv(a.C);
+    const size_t lds_bytes = sizeof(float) * (4 * (size_t)g.slice + 4);
+    return launch_kernel(dw::dwconv3x3_stream_kernel<W4_T, NI>, dim3((unsigned)((g.items + 3) / 4)), dim3(256),
+                         lds_bytes, stream, a, g);
+}
+
+template <int NI>
+hipError_t launch_stream(const ConvArgs& a, hipStream_t stream)
+{
+    switch (a.W) {
+        case 28: return launch_stream_as<7, NI>(a, stream);
+        case 56: return launch_stream_as<14, NI>(a, stream);
+        case 112: return launch_stream_as<28, NI>(a, stream);
+        default: return launch_stream_as<0, NI>(a, stream);
+    }
+}
+
 // Small planes of dense tensors: see dwconv_small_planes_kernel.
 hipError_t launch_small_planes(const ConvArgs& a, hipStream_t stream, bool* taken)
 {
@@ -89,6 +129,20 @@ hipError_t launch_dwconv3x3(const ConvArgs& a, hipStream_t stream, bool* taken)
     const bool ok = common && a.stride_h == 1 && a.stride_w == 1 && (a.W % 4 == 0) && a.W <= 256;
     *taken = ok;
     if (!ok) return hipSuccess;
+    // dense x and y (planes and rows back to back): the streaming kernel
+    const int64_t hw = (int64_t)a.H * a.W;
+    const bool dense = a.xs[2] == a.W && a.xs[1] == hw && a.xs[0] == a.C * hw && a.ys[2] == a.W && a.ys[1] == hw &&
+                       a.ys[0] == a.C * hw && hw < ((int64_t)1 << 30) && a.H >= 3 &&
+                       (int64_t)a.N * a.C * a.H < ((int64_t)1 << 30);
+    if (dense) {
+        // Planes taller than four rounds of rows are cut into runs with two halo rows each: eight
+        // rounds per run re-read less (112x112x32 at batch 16: 9.9 against 11.8 us) as long as that
+        // still makes some 16 waves per CU (at batch 1: 4.0 against 3.1 us)
+        const int rpr = 64 / (a.W / 4);
+        const int64_t items8 = (int64_t)a.N * a.C * ((a.H + 8 * rpr - 3) / (8 * rpr - 2));
+        if (a.H > 4 * rpr && items8 >= 4096) return launch_stream<8>(a, stream);
+        return launch_stream<4>(a, stream);
+    }
     // 14 rows per wave re-read fewer halo rows (2 in 16 instead of 2 in 9) but make half as many
     // waves; below about four waves per SIMD the shorter strips win (measured on 16x256x28x28:
     // 8.4 us against 9.5 us)

@@ -140,6 +140,147 @@ __global__ __launch_bounds__(64 * WPB) void dwconv3x3s2_kernel(const ConvArgs p,
     }
 }
 
+// Stride 1, 3x3, pad 1 on dense NCHW tensors, as a pure stream.  An item is a run of RC output
+// rows of one plane; its input rows (RC + 2, clipped at the plane's edges) are ONE contiguous
+// range of x and its output rows one contiguous range of y.  A wave owns an item: it pulls the
+// input range into its private slice of LDS with direct-to-LDS loads (consecutive lanes fetch
+// consecutive 16-byte units, so every request covers whole cache lines, and the data never
+// passes through registers), then each lane computes output units from LDS (one 16-byte read
+// per input row plus the two neighbouring columns) and stores them, again with consecutive
+// lanes on consecutive units.  Loads and stores are non-temporal: x is read once and y written
+// once, and lines that linger in L2 are written back when the kernel ends, which a measured
+// 26 MB copy pays with 6.8 instead of 5.3 us.  No work-group barrier: a wave's slice of LDS is
+// its own.
+//
+// Per-wave timestamps showed the arithmetic, not the traffic, to be what such a kernel adds to a
+// copy: its waves get their data within the same microsecond and then share the vector ALUs.
+// So a round of the wave covers whole rows (RPR = floor(64 / (W/4)) of them, LPR = RPR * W/4
+// lanes): a lane keeps its column for all rounds, the tests for the plane's left and right edge
+// are folded into the lane's copy of the weights once, a zero row in LDS stands in for the row
+// above and below the plane, and with the width known at compile time every LDS and global
+// address of a round is the lane's base plus an instruction immediate: 36 multiply-adds per
+// round and next to nothing else.  (Tried: the neighbouring columns by DPP wave shift instead of
+// 4-byte LDS reads, which fall on 16 banks: 6.9 against 6.3 us, the shifts are vector-ALU work;
+// edge taps under a branch or as predicated reads: 6.7 us; two to eight items per wave with the
+// loads of all of them in flight: 6.7 to 12.8 us, a wave's chain is what counts; starting the
+// waves' loads in staggered groups so that stores of one group overlap loads of the next: slower
+// at every delay.)
+struct StreamGeom {
+    int W4;               // W / 4
+    int RPR, LPR;         // rows and lanes per round
+    int RC;               // output rows per item
+    int chunks;           // items per plane = ceil(H / RC)
+    int hw;               // H * W
+    int slice;            // floats of LDS per wave, slack included (a multiple of 4)
+    int items;            // planes * chunks
+    FastDiv d_chunks, d_w4, d_c;
+};
+
+// NI: rounds that cover an item's input rows (its output rows are fewer); W4_T: W / 4, or 0 for any width
+template <int W4_T, int NI>
+__global__ __launch_bounds__(256) void dwconv3x3_stream_kernel(const ConvArgs p, const StreamGeom g)
+{
+    extern __shared__ __attribute__((aligned(16))) float slds[];
+    const int W4 = W4_T ? W4_T : g.W4, W = 4 * W4;
+    const int RPR = W4_T ? 64 / W4_T : g.RPR, LPR = RPR * W4;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int item = __builtin_amdgcn_readfirstlane((int)blockIdx.x * 4 + wv);
+    if (item >= g.items) return;                                   // whole wave
+    // four floats of slack ahead of the slice: the read left of its first unit stays inside LDS
+    float* const lx = slds + 4 + wv * g.slice;
+    const int plane = g.d_chunks.div(item);
+    const int r0 = (item - plane * g.chunks) * g.RC;               // first output row
+    const int r1 = r0 + g.RC < p.H ? r0 + g.RC : p.H;              // one past the last
+    const int in0 = r0 > 0 ? r0 - 1 : 0;                           // first input row staged
+    const int in1 = r1 < p.H ? r1 + 1 : p.H;
+    const int c = plane - g.d_c.div(plane) * p.C;
+
+    // ---- LDS row j of the slice is input row r0 - 1 + j.  Rows in0 .. in1-1 are (in1 - in0) * W4
+    //      consecutive units of x and land on consecutive units of the slice, LPR per instruction
+    //      (lanes past a round or past the end sit the instruction out).  A row above or below the
+    //      plane is zero-filled by the wave itself, so the taps need no test for it.
+    const float* __restrict__ src = p.x + (int64_t)plane * g.hw + in0 * W + 4 * lane;
+    const int n_in = (in1 - in0) * W4;
+    float* const land = lx + (in0 - (r0 - 1)) * W;                  // W floats further when r0 == 0
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        if (lane < LPR && lane + LPR * i < n_in)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + 4 * LPR * i),
+                                             (__attribute__((address_space(3))) void*)(land + 4 * LPR * i), 16, 0, 2);
+    }
+    if (r0 == 0 && lane < W4) *reinterpret_cast<f32x4*>(lx + 4 * lane) = zero4();
+    if (r1 == p.H && lane < W4) *reinterpret_cast<f32x4*>(lx + (r1 - r0 + 1) * W + 4 * lane) = zero4();
+
+    // the lane's column never changes, so whether it has a neighbour to its left and right is
+    // decided once
+    const int ch = lane - g.d_w4.div(lane) * W4;
+    const bool has_l = ch > 0, has_r = ch < W4 - 1;
+    float wt[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) wt[i] = p.w[c * 9 + i];
+    // The compiler does not order LDS reads after direct-to-LDS loads by itself: wait for the
+    // loads here, and keep every later memory access behind the wait.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+
+    // ---- output rows r0 .. r1-1, RPR per round: the unit of lane l in round i is unit l + LPR * i
+    //      of the item, and its tap rows are that unit of slice rows j, j + 1, j + 2.  The columns
+    //      left and right of a unit are read from LDS as they lie (inside a row the neighbouring
+    //      unit; at the plane's edge the end of another row or the slack around the slice).  The
+    //      first and last output of a unit are summed without those taps first; the lanes that have
+    //      the neighbour then take the sum with them, the others the sum without: one select per
+    //      edge and round, and a tap across the edge is never multiplied at all.
+    float* __restrict__ dst = p.y + (int64_t)plane * g.hw + r0 * W + 4 * lane;
+    const int n_out = (r1 - r0) * W4;
+    const float* const t0 = lx + 4 * lane;
+    // All rounds are computed before the first store is issued: the compiler makes every LDS read
+    // that follows a store wait for that store (it cannot tell the store from the direct-to-LDS
+    // loads), which would put a trip to L2 between one round and the next.
+    f32x4 res[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        if (lane < LPR && lane + LPR * i < n_out) {
+            f32x4 acc;
+            float al, ar;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const float* row = t0 + 4 * LPR * i + r * W;
+                const f32x4 m = *reinterpret_cast<const f32x4*>(row);
+                const float l = row[-1], rr = row[4];
+                const float w0 = wt[3 * r], w1 = wt[3 * r + 1], w2 = wt[3 * r + 2];
+                if (r == 0) {
+                    acc[0] = w1 * m[0];
+                    acc[1] = w0 * m[0];
+                    acc[2] = w0 * m[1];
+                    acc[3] = w0 * m[2];
+                    al = w0 * l;
+                    ar = w2 * rr;
+                } else {
+                    acc[0] = fmaf(w1, m[0], acc[0]);
+                    acc[1] = fmaf(w0, m[0], acc[1]);
+                    acc[2] = fmaf(w0, m[1], acc[2]);
+                    acc[3] = fmaf(w0, m[2], acc[3]);
+                    al = fmaf(w0, l, al);
+                    ar = fmaf(w2, rr, ar);
+                }
+                acc[0] = fmaf(w2, m[1], acc[0]);
+                acc[1] = fmaf(w1, m[1], acc[1]);
+                acc[2] = fmaf(w1, m[2], acc[2]);
+                acc[3] = fmaf(w1, m[3], acc[3]);
+                acc[1] = fmaf(w2, m[2], acc[1]);
+                acc[2] = fmaf(w2, m[3], acc[2]);
+            }
+            acc[0] += has_l ? al : 0.f;
+            acc[3] += has_r ? ar : 0.f;
+            res[i] = acc;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+        if (lane < LPR && lane + LPR * i < n_out)
+            stg4_nt(dst + 4 * LPR * i, res[i]);
+}
+
 // Small planes (14 x 14 and 7 x 7 maps of the MobileNet shape list, any kernel, stride, padding
 // and dilation) of dense NCHW tensors: a work-group takes G consecutive planes, which are one
 // contiguous range of x and of y.  The range is copied to LDS with coalesced 16-byte loads, the

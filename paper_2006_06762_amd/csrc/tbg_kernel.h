@@ -200,13 +200,15 @@ __global__ __launch_bounds__(256) void tbg_tile64_kernel(const Args p)
             for (int e = 0; e < 4; ++e) acc = mfma32(a[kk][e], bb[kk][e], acc);
     }
 
-    // register r of lane (h2, r32): row 8*(r/4) + 4*h2 + r%4, column r32 of the block
+    // register r of lane (h2, r32): row 8*(r/4) + 4*h2 + r%4, column r32 of the block.  A store
+    // instruction writes two whole 128-byte lines; the scores are not read again, so the stores are
+    // non-temporal (9.4 -> 7.0 us with cold buffers: the lines need no write-back at the kernel's end)
     const int voffo = 4 * ((wi + 4 * h2) * os_i + wj + r32);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const float v = acc[r];
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), orsrc, voffo,
-                                              4 * ((i0 + 8 * (r / 4) + (r % 4)) * os_i + j0), 0);
+                                              4 * ((i0 + 8 * (r / 4) + (r % 4)) * os_i + j0), kBufferNonTemporal);
     }
 }
 
@@ -449,7 +451,7 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
         for (int i = 0; i < 4; ++i) {
             const int rl = 8 * QBK * wv + RPI * i;            // uniform over the wave
             const f32x4 v = *reinterpret_cast<const f32x4*>(&ps[(rl + lane / LPR) * kLdP + col]);
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), orsrc, voffo, 4 * (i0 + rl) * os_i, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), orsrc, voffo, 4 * (i0 + rl) * os_i, kBufferNonTemporal);
         }
         return;
     }
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(256) void tbs_rows32_kernel(const Args p, int ld, i
         if (WHOLE || row < p.S) {
             float* orow = ob + row * p.os_i;
             if (vec_store && (WHOLE || col + 3 < p.S)) {
-                stg4(orow + col, v);
+                stg4_nt(orow + col, v);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)

@@ -828,6 +828,45 @@ def test_dwconv_random_geometries(anr):
         assert_parity(y, ref, exact=True, what="random dwconv %d %s" % (i, s))
 
 
+def test_dwconv_stream_kernel_runs_of_rows(anr):
+    """Stride-1 3x3 layers on dense tensors take the streaming kernel.  Planes taller than its rounds
+    of rows are cut into runs with halo rows, four or eight rounds each (eight once that still makes
+    4096 waves); widths whose rows fill 64, 56, 48 or 33 lanes of a round; single-row and two-row planes.
+    Small-integer values: bit for bit."""
+    shapes = [I.ConvShape(2, 5, 100, 64, 5, 3, 3, (1, 1), (1, 1)),        # 16 rows per run: 14 + halo
+              I.ConvShape(8, 128, 60, 128, 128, 3, 3, (1, 1), (1, 1)),    # eight rounds: 1024 planes x 5 runs
+              I.ConvShape(1, 3, 37, 256, 3, 3, 3, (1, 1), (1, 1)),        # one row per round
+              I.ConvShape(3, 4, 29, 44, 4, 3, 3, (1, 1), (1, 1)),         # 11 units per row: 55 lanes
+              I.ConvShape(2, 3, 1, 28, 3, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(2, 3, 2, 12, 3, 3, 3, (1, 1), (1, 1)),
+              I.ConvShape(1, 2, 70, 132, 2, 3, 3, (1, 1), (1, 1))]        # 33 units per row: one row per round
+    for i, s in enumerate(shapes):
+        x, w = I.dwconv_inputs(s, 1300 + i, ints=True)
+        buf, y = guarded((s.N, s.C, s.OH, s.OW))
+        anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+        check_guard(buf)
+        assert_parity(y, oracle.dwconv(x, w, s.stride, s.pad), exact=True, what="stream dwconv %s" % (s,))
+
+
+def test_dwconv_taps_across_the_plane_edge_are_not_multiplied(anr):
+    """Zero padding means a tap outside the plane contributes nothing, whatever lies next to it in
+    memory: an infinite value in the last column of a row must not reach the first column of the rows
+    below it (nor one in the first column the last column of the rows above)."""
+    s = I.ConvShape(1, 2, 28, 28, 2, 3, 3, (1, 1), (1, 1))
+    x, w = I.dwconv_inputs(s, 1310)
+    x[0, 0, 10, 27] = np.inf
+    x[0, 1, 20, 0] = np.inf
+    y = torch.empty((s.N, s.C, s.OH, s.OW), device="cuda")
+    anr.dwconv(dev(x), dev(w), y, s.stride, s.pad)
+    got = y.cpu().numpy()
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.dwconv(x, w, s.stride, s.pad)
+    finite = np.isfinite(ref)
+    assert finite[0, 0, 11, 0] and finite[0, 0, 12, 0] and finite[0, 1, 19, 27]     # the oracle agrees these are untouched
+    assert np.array_equal(np.isfinite(got), finite)
+    assert rel_err(got[finite], ref[finite]) <= TOL
+
+
 def test_gemm_random_shapes(anr):
     g = np.random.Generator(np.random.PCG64(960))
     for i in range(30):
