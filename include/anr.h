@@ -172,6 +172,46 @@ anr_status anr_conv2d(const anr_conv_desc *desc, const float *x, const float *w,
 anr_status anr_conv2d_noalloc(const anr_conv_desc *desc, const float *x, const float *w, float *y,
                               void *hip_stream);
 
+/*
+ * Pre-packed constants (Sec. 4.2 "Random annotation": the layouts of constant tensors
+ * are rewritten ahead of time to fit the tile structure, at no run-time cost, because
+ * convolution weights are constants for inference; Sec. 7.3 credits this rewrite with
+ * about 40 % of the ResNet-50 result).  x and y stay in their plain NCHW layout (Sec. 7.1:
+ * inputs and outputs must not be packed); only the weights, and for ConvLayer the folded
+ * batch-norm constants, are rewritten, once, into a `pack` that the caller keeps.
+ *
+ *   anr_conv2d_packed_size   bytes of the pack for `desc` (a function of the descriptor
+ *                            only, `route` included).
+ *   anr_conv2d_pack_weights  writes the pack: the weights w (OIHW [K, C/groups, R, S]) in
+ *                            the order in which the kernel planned for `desc` stages them
+ *                            (for the 3x3 patch-staging kernel: per channel tile and chunk
+ *                            of input channels one contiguous image of its LDS buffer; for
+ *                            every other plan a plain copy), preceded by scale[K], shift[K]
+ *                            = gamma/sqrt(var+eps), beta - mean*scale in fp32 when the four
+ *                            batch-norm vectors are given (all four or none; none: that part
+ *                            of the pack is left unwritten).  `packed`: device memory,
+ *                            256-byte aligned, packed_bytes >= anr_conv2d_packed_size (else
+ *                            ANR_ERR_WORKSPACE).  Enqueued on the stream like any call.
+ *   anr_conv2d_packed        anr_conv2d with the pack in place of w: same results bit for
+ *   anr_conv_bn_relu_packed  bit (the same products are summed in the same order), same
+ *                            workspace rule.  The descriptor must equal the one the pack
+ *                            was made for (not checked: the pack lives in device memory);
+ *                            anr_conv_bn_relu_packed needs a pack made with the batch-norm
+ *                            vectors.  A pack in the patch kernel's order presumes that
+ *                            kernel's alignment rules for x (16-byte aligned pointer,
+ *                            strides multiples of 4): a call with another x returns
+ *                            ANR_ERR_INVALID_ARG.
+ */
+anr_status anr_conv2d_packed_size(const anr_conv_desc *desc, size_t *bytes);
+anr_status anr_conv2d_pack_weights(const anr_conv_desc *desc, const float *w,
+                                   const float *gamma, const float *beta,
+                                   const float *mean, const float *var, float eps,
+                                   void *packed, size_t packed_bytes, void *hip_stream);
+anr_status anr_conv2d_packed(const anr_conv_desc *desc, const float *x, const void *packed, float *y,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+anr_status anr_conv_bn_relu_packed(const anr_conv_desc *desc, const float *x, const void *packed, float *y,
+                                   void *ws, size_t ws_bytes, void *hip_stream);
+
 /* ConvLayer (Sec. 7.2): the convolution above, then inference batch
  * normalisation per output channel, gamma*(v-mean)/sqrt(var+eps)+beta, then
  * ReLU, in one kernel (Table 1 rule 4: element-wise consumers are fused into

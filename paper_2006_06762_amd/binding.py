@@ -27,7 +27,8 @@ ANR_OK, ANR_ERR_NULL, ANR_ERR_INVALID_ARG, ANR_ERR_UNSUPPORTED, ANR_ERR_WORKSPAC
 ANR_LAYOUT_NCHW = 0
 ANR_OP_GEMM, ANR_OP_CONV2D, ANR_OP_CONV_BN_RELU, ANR_OP_DWCONV, ANR_OP_TBG, ANR_OP_TBS, ANR_OP_NRM = range(7)
 
-EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
+EXPORTS = ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv2d_packed_size", "anr_conv2d_pack_weights",
+           "anr_conv2d_packed", "anr_conv_bn_relu_packed", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs", "anr_nrm",
            "anr_workspace_size", "anr_conv2d_route", "anr_status_string", "anr_version", "anr_last_hip_error",
            "anr_last_hip_error_string")
 
@@ -76,6 +77,11 @@ _vp = ctypes.c_void_p
 _lib.anr_gemm.argtypes = [ctypes.POINTER(GemmDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_conv2d.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_conv2d_noalloc.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp]
+_lib.anr_conv2d_packed_size.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ctypes.c_size_t)]
+_lib.anr_conv2d_pack_weights.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp,
+                                         ctypes.c_size_t, _vp]
+_lib.anr_conv2d_packed.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.anr_conv_bn_relu_packed.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_conv_bn_relu.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float,
                                   _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_dwconv.argtypes = [ctypes.POINTER(ConvDesc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -84,7 +90,8 @@ _lib.anr_tbs.argtypes = [ctypes.POINTER(TbgDesc), _vp, _vp, _vp, _vp, ctypes.c_s
 _lib.anr_nrm.argtypes = [ctypes.POINTER(NrmDesc), _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.anr_workspace_size.argtypes = [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_size_t)]
 _lib.anr_conv2d_route.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ConvRoute)]
-for _name in ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
+for _name in ("anr_gemm", "anr_conv2d", "anr_conv2d_noalloc", "anr_conv2d_packed_size", "anr_conv2d_pack_weights",
+              "anr_conv2d_packed", "anr_conv_bn_relu_packed", "anr_conv_bn_relu", "anr_dwconv", "anr_tbg", "anr_tbs",
               "anr_workspace_size"):
     getattr(_lib, _name).restype = ctypes.c_int
 _lib.anr_status_string.argtypes = [ctypes.c_int]
@@ -235,6 +242,50 @@ def conv2d_noalloc(x, w, y, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1, rou
                   route=route)
     _check(_lib.anr_conv2d_noalloc(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _stream()), "anr_conv2d_noalloc")
     return y
+
+
+def conv2d_packed_size(desc: ConvDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.anr_conv2d_packed_size(ctypes.byref(desc), ctypes.byref(n)), "anr_conv2d_packed_size")
+    return int(n.value)
+
+
+def conv2d_pack_weights(x_shape, w, stride=(1, 1), pad=(0, 0), bn=None, eps=0.0, dil=(1, 1), groups=1,
+                        route=ANR_CONV_ROUTE_AUTO):
+    """Packs w (and, with bn = (gamma, beta, mean, var), the folded batch norm) for the layer that
+    x_shape, w and the geometry describe.  Returns (descriptor, pack): the pack is a new uint8 CUDA
+    tensor (torch's allocations are 256-byte aligned) to hand to conv2d_packed / conv_bn_relu_packed."""
+    K, _, R, S = w.shape
+    if not w.is_contiguous():
+        raise ValueError("weights must be packed OIHW")
+    d = conv_desc(tuple(x_shape), K, R, S, stride, pad, dil=dil, groups=groups, route=route)
+    pack = torch.empty(conv2d_packed_size(d), dtype=torch.uint8, device=w.device)
+    vecs = [None] * 4 if bn is None else [_ptr(v) for v in bn]
+    _check(_lib.anr_conv2d_pack_weights(ctypes.byref(d), _ptr(w), vecs[0], vecs[1], vecs[2], vecs[3],
+                                        ctypes.c_float(eps), ctypes.c_void_p(pack.data_ptr()), pack.numel(), _stream()),
+           "anr_conv2d_pack_weights")
+    return d, pack
+
+
+def _run_packed(fn, name, desc, x, pack, y, ws):
+    d = ConvDesc.from_buffer_copy(desc)
+    xs, ys = _conv_strides(x), _conv_strides(y)
+    d.x_stride = (ctypes.c_int64 * 4)(*(xs or (0, 0, 0, 0)))
+    d.y_stride = (ctypes.c_int64 * 4)(*(ys or (0, 0, 0, 0)))
+    op = ANR_OP_CONV2D if fn is _lib.anr_conv2d_packed else ANR_OP_CONV_BN_RELU
+    wp, wb = _workspace(op, d, ws)
+    _check(fn(ctypes.byref(d), _ptr(x), ctypes.c_void_p(pack.data_ptr()), _ptr(y), wp, wb, _stream()), name)
+    return y
+
+
+def conv2d_packed(desc, x, pack, y, ws=None):
+    """conv2d with weights from conv2d_pack_weights (desc: the descriptor it returned)."""
+    return _run_packed(_lib.anr_conv2d_packed, "anr_conv2d_packed", desc, x, pack, y, ws)
+
+
+def conv_bn_relu_packed(desc, x, pack, y, ws=None):
+    """conv + batch norm + ReLU with a pack made with bn=(gamma, beta, mean, var)."""
+    return _run_packed(_lib.anr_conv_bn_relu_packed, "anr_conv_bn_relu_packed", desc, x, pack, y, ws)
 
 
 def conv_bn_relu(x, w, gamma, beta, mean, var, eps, y, stride=(1, 1), pad=(0, 0), ws=None, dil=(1, 1), groups=1,

@@ -83,12 +83,18 @@ struct ConvArgs {
     int OH, OW;
     int64_t xs[4];   // element strides n,c,h,w (w stride is 1)
     int64_t ys[4];
-    // fused epilogue (ConvLayer): nullptr gamma means plain convolution
+    // fused epilogue (ConvLayer): nullptr gamma means plain convolution (in a pre-packed call gamma
+    // is only this marker: the constants come from scale_shift)
     const float* gamma;
     const float* beta;
     const float* mean;
     const float* var;
     float eps;
+    // pre-packed constants (anr_conv2d_pack_weights): the weights in the order the kernel chosen
+    // for this descriptor stages them (w is then the OIHW copy inside the pack, or null when the
+    // pack holds no such copy), and the folded batch-norm scale[K] then shift[K]; null: not packed
+    const float* wpack;
+    const float* scale_shift;
     // caller's workspace (device memory, 16-byte aligned) for the split-K partial tiles
     float* ws;
     size_t ws_bytes;
@@ -99,6 +105,18 @@ size_t conv2d_workspace_bytes(const ConvArgs& a);
 // Plans once, checks a.ws / a.ws_bytes against the plan, launches.  *ws_fault: 0 fine, 1 the
 // workspace is missing or too small, 2 it is not 16-byte aligned (nothing is enqueued then).
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault);
+
+// Pre-packed weights.  The pack is [scale K | shift K, padded to 64 floats][weights]; for a plan
+// of the patch-staging kernel the weights are that kernel's LDS images, chunk after chunk
+// (`patch_layout`), for every other plan a plain OIHW copy.
+struct ConvPackLayout {
+    bool patch_layout;
+    size_t ss_floats;        // floats ahead of the weights
+    size_t w_floats;         // floats of the weights part
+};
+ConvPackLayout conv2d_pack_layout(const ConvArgs& a);
+// Writes the pack for `a` (a.w: OIHW weights; a.gamma ..: batch-norm vectors or null) to `pack`.
+hipError_t launch_conv2d_pack(const ConvArgs& a, float* pack, hipStream_t stream);
 hipError_t launch_dwconv(const ConvArgs& a, hipStream_t stream);
 
 // The library's static scratch array (static_scratch.hip): device address of the current

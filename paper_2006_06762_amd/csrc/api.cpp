@@ -95,6 +95,8 @@ anr::ConvArgs make_conv_args(const anr_conv_desc* d, const ConvGeom& g, const fl
     for (int i = 0; i < 4; ++i) { a.xs[i] = g.xs[i]; a.ys[i] = g.ys[i]; }
     a.gamma = a.beta = a.mean = a.var = nullptr;
     a.eps = 0.f;
+    a.wpack = nullptr;
+    a.scale_shift = nullptr;
     a.ws = nullptr;
     a.ws_bytes = 0;
     return a;
@@ -249,6 +251,77 @@ anr_status anr_conv2d_noalloc(const anr_conv_desc* d, const float* x, const floa
     const hipError_t e = anr::static_scratch(&scratch, &scratch_bytes);
     if (e != hipSuccess) return launch_status(e);
     return run_conv2d(&a, scratch, scratch_bytes, hip_stream);
+}
+
+anr_status anr_conv2d_packed_size(const anr_conv_desc* d, size_t* bytes)
+{
+    if (!bytes) return ANR_ERR_NULL;
+    ConvGeom g;
+    const anr_status st = check_conv(d, false, &g);
+    if (st != ANR_OK) return st;
+    const anr::ConvArgs a = make_conv_args(d, g, nullptr, nullptr, nullptr);
+    const anr::ConvPackLayout l = anr::conv2d_pack_layout(a);
+    *bytes = sizeof(float) * (l.ss_floats + l.w_floats);
+    return ANR_OK;
+}
+
+anr_status anr_conv2d_pack_weights(const anr_conv_desc* d, const float* w, const float* gamma, const float* beta,
+                                   const float* mean, const float* var, float eps, void* packed, size_t packed_bytes,
+                                   void* hip_stream)
+{
+    ConvGeom g;
+    anr_status st = check_conv(d, false, &g);
+    if (st != ANR_OK) return st;
+    if (!w || !packed) return ANR_ERR_NULL;
+    // batch-norm vectors: all four or none
+    const int given = (gamma != nullptr) + (beta != nullptr) + (mean != nullptr) + (var != nullptr);
+    if (given != 0 && given != 4) return ANR_ERR_NULL;
+    if (given == 4 && !std::isfinite(eps)) return ANR_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(packed) & 255) return ANR_ERR_INVALID_ARG;
+    anr::ConvArgs a = make_conv_args(d, g, nullptr, w, nullptr);
+    const anr::ConvPackLayout l = anr::conv2d_pack_layout(a);
+    if (packed_bytes < sizeof(float) * (l.ss_floats + l.w_floats)) return ANR_ERR_WORKSPACE;
+    a.gamma = gamma; a.beta = beta; a.mean = mean; a.var = var; a.eps = eps;
+    return launch_status(anr::launch_conv2d_pack(a, static_cast<float*>(packed), static_cast<hipStream_t>(hip_stream)));
+}
+
+namespace {
+anr_status run_packed(const anr_conv_desc* d, const float* x, const void* packed, float* y, bool fused, void* ws,
+                      size_t ws_bytes, void* hip_stream)
+{
+    ConvGeom g;
+    const anr_status st = check_conv(d, false, &g);
+    if (st != ANR_OK) return st;
+    if (!x || !packed || !y) return ANR_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) & 255) return ANR_ERR_INVALID_ARG;
+    anr::ConvArgs a = make_conv_args(d, g, x, nullptr, y);
+    const anr::ConvPackLayout l = anr::conv2d_pack_layout(a);
+    const float* pack = static_cast<const float*>(packed);
+    if (l.patch_layout) {
+        a.wpack = pack + l.ss_floats;
+        // the pack presumes the plan for 16-byte aligned x: a view that kernel cannot read cannot use it
+        if (!anr::conv2d_igemm_takes(a)) return ANR_ERR_INVALID_ARG;
+    } else {
+        a.w = pack + l.ss_floats;
+    }
+    if (fused) {
+        a.gamma = pack;            // marker: fused epilogue, constants from scale_shift
+        a.scale_shift = pack;
+    }
+    return run_conv2d(&a, ws, ws_bytes, hip_stream);
+}
+}  // namespace
+
+anr_status anr_conv2d_packed(const anr_conv_desc* d, const float* x, const void* packed, float* y, void* ws,
+                             size_t ws_bytes, void* hip_stream)
+{
+    return run_packed(d, x, packed, y, false, ws, ws_bytes, hip_stream);
+}
+
+anr_status anr_conv_bn_relu_packed(const anr_conv_desc* d, const float* x, const void* packed, float* y, void* ws,
+                                   size_t ws_bytes, void* hip_stream)
+{
+    return run_packed(d, x, packed, y, true, ws, ws_bytes, hip_stream);
 }
 
 anr_status anr_conv_bn_relu(const anr_conv_desc* d, const float* x, const float* w, const float* gamma,

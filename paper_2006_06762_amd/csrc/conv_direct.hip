@@ -41,8 +41,8 @@ __global__ __launch_bounds__(256) void conv2d_direct_kernel(const ConvArgs p, in
         }
     }
     if (p.gamma) {
-        const float scale = p.gamma[k] / sqrtf(p.var[k] + p.eps);
-        const float shift = p.beta[k] - p.mean[k] * scale;
+        const float scale = p.scale_shift ? p.scale_shift[k] : p.gamma[k] / sqrtf(p.var[k] + p.eps);
+        const float shift = p.scale_shift ? p.scale_shift[p.K + k] : p.beta[k] - p.mean[k] * scale;
         acc = fmaxf(fmaf(acc, scale, shift), 0.f);
     }
     p.y[n * p.ys[0] + k * p.ys[1] + oh * p.ys[2] + ow] = acc;

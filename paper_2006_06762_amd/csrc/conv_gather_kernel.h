@@ -66,6 +66,11 @@ struct Plan {
 // Inference batch norm of output channel co as one multiply-add: y = v * scale + shift.
 __device__ __forceinline__ void bn_constants(const ConvArgs& p, int co, float* scale, float* shift)
 {
+    if (p.scale_shift) {            // folded ahead of time (pre-packed call)
+        *scale = p.scale_shift[co];
+        *shift = p.scale_shift[p.K + co];
+        return;
+    }
     *scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
     *shift = p.beta[co] - p.mean[co] * *scale;
 }

@@ -71,13 +71,15 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
 constexpr int kMinTunedWorkGroups = 112;
 
 struct IgemmPlan {
-    int variant;     // index into the variant table, -1: the kernel does not take the call
+    int variant;     // 0 V224x64, 1 V224x32, 2 V128x64, 3 V64x64, 4 V224x32c16; -1: the kernel does not take the call
     Geom g;
     size_t lds;
 };
 
 // The one planning pass of a call: variant, geometry and LDS size, with the descriptor's route
-// applied (1: whenever a variant runs the shape; 2: never; 0: with enough output tiles).
+// applied (1: whenever a variant runs the shape; 2: never; 0: with enough output tiles).  Depends
+// on the descriptor and on the alignment of x and w only (null pointers count as aligned), so a
+// pack made for a descriptor fits every later call with it.
 void plan_igemm(const ConvArgs& a, IgemmPlan* p)
 {
     p->variant = -1;
@@ -86,6 +88,16 @@ void plan_igemm(const ConvArgs& a, IgemmPlan* p)
     if (best < 0) return;
     if (a.route != 1 && (int64_t)p->g.tiles_m * p->g.tiles_n < kMinTunedWorkGroups) return;
     p->variant = best;
+    if (best == 1) {
+        // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
+        Geom g16;
+        size_t lds16 = 0;
+        if (V224x32c16::plan(a, &g16, &lds16) && g16.RSL == 36 && g16.P == 432 && V224x32c16::units_per_thread(g16) <= 6) {
+            p->variant = 4;
+            p->g = g16;
+            p->lds = lds16;
+        }
+    }
 }
 
 hipError_t launch_igemm_plan(const ConvArgs& a, const IgemmPlan& p, hipStream_t stream)
@@ -97,20 +109,65 @@ hipError_t launch_igemm_plan(const ConvArgs& a, const IgemmPlan& p, hipStream_t 
         case 0:
             if (try_fixed<V224x64, 3, 64, 384>(a, g, lds, stream, &err)) return err;    // 56x56 maps, stride 1
             return V224x64::launch(a, g, lds, stream);
-        case 1: {
-            // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
-            Geom g8;
-            size_t lds8 = 0;
-            if (V224x32c16::plan(a, &g8, &lds8) &&
-                try_fixed<V224x32c16, 6, 36, 432>(a, g8, lds8, stream, &err))
-                return err;
-        }
+        case 4: return V224x32c16::launch_fixed<6, 36, 432>(a, g, lds, stream);          // 28x28 maps, stride 1
+        case 1:
             if (try_fixed<V224x32, 6, 36, 432>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 1
             if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
             return V224x32::launch(a, g, lds, stream);
         case 2: return V128x64::launch(a, g, lds, stream);
         default: return V64x64::launch(a, g, lds, stream);
     }
+}
+
+// Floats of the packed weights of plan p, and its channel tile and chunk (output channels x input channels).
+int64_t packed_floats(const ConvArgs& a, const IgemmPlan& p, int* bn, int* ck)
+{
+    switch (p.variant) {
+        case 0: *bn = V224x64::BN; *ck = V224x64::CK; return V224x64::packed_floats(a);
+        case 1: *bn = V224x32::BN; *ck = V224x32::CK; return V224x32::packed_floats(a);
+        case 2: *bn = V128x64::BN; *ck = V128x64::CK; return V128x64::packed_floats(a);
+        case 3: *bn = V64x64::BN; *ck = V64x64::CK; return V64x64::packed_floats(a);
+        case 4: *bn = V224x32c16::BN; *ck = V224x32c16::CK; return V224x32c16::packed_floats(a);
+        default: *bn = *ck = 0; return 0;
+    }
+}
+
+// Writes the pack's weights part in the patch kernel's order: for channel tile t and chunk q the
+// LDS image of the tile's BN channels, KC = CK * 9 weights each in OIHW order followed by the two
+// floats of padding of an LDS row; channels past K are zero.  One thread per float.
+__global__ __launch_bounds__(256) void conv_pack_patch_kernel(const float* __restrict__ w, float* __restrict__ out,
+                                                              int K, int C, int bn, int ck, int64_t total)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int kc = ck * 9, ws = kc + 2, nchunks = C / ck;
+    const int j = (int)(idx % ws);
+    int64_t t = idx / ws;
+    const int col = (int)(t % bn);
+    t /= bn;
+    const int chunk = (int)(t % nchunks);
+    const int tile = (int)(t / nchunks);
+    const int co = tile * bn + col;
+    out[idx] = (j < kc && co < K) ? w[((int64_t)co * C + (int64_t)chunk * ck) * 9 + j] : 0.f;
+}
+
+// Plain copy (plans other than the patch kernel keep OIHW order).
+__global__ __launch_bounds__(256) void conv_pack_copy_kernel(const float* __restrict__ w, float* __restrict__ out, int64_t total)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx < total) out[idx] = w[idx];
+}
+
+// Folded batch norm, the same fp32 arithmetic as the kernels' own epilogue: scale, then shift.
+__global__ __launch_bounds__(256) void conv_pack_bn_kernel(const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                           const float* __restrict__ mean, const float* __restrict__ var,
+                                                           float eps, float* __restrict__ out, int K)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    const float scale = gamma[k] / sqrtf(var[k] + eps);
+    out[k] = scale;
+    out[K + k] = beta[k] - mean[k] * scale;
 }
 
 }  // namespace
@@ -127,7 +184,7 @@ bool describe_conv2d_igemm(const ConvArgs& a, ConvRoute* r)
     IgemmPlan p;
     plan_igemm(a, &p);
     if (p.variant < 0) return false;
-    static const int kTileM[4] = {224, 224, 128, 64}, kTileN[4] = {64, 32, 64, 64};
+    static const int kTileM[5] = {224, 224, 128, 64, 224}, kTileN[5] = {64, 32, 64, 64, 32};
     r->kernel = 1;
     r->tile_m = kTileM[p.variant];
     r->tile_n = kTileN[p.variant];
@@ -155,6 +212,46 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
 size_t conv2d_workspace_bytes(const ConvArgs& a)
 {
     return conv2d_igemm_takes(a) ? 0 : conv2d_gather_workspace_bytes(a);
+}
+
+ConvPackLayout conv2d_pack_layout(const ConvArgs& a)
+{
+    ConvPackLayout l{};
+    l.ss_floats = ((size_t)2 * a.K + 63) / 64 * 64;
+    // the plan for aligned pointers, whatever a.x and a.w hold at pack time
+    ConvArgs b = a;
+    b.x = nullptr;
+    b.w = nullptr;
+    b.wpack = nullptr;
+    IgemmPlan p;
+    plan_igemm(b, &p);
+    int bn = 0, ck = 0;
+    const int64_t pf = packed_floats(b, p, &bn, &ck);
+    l.patch_layout = p.variant >= 0 && pf < ((int64_t)1 << 30);
+    l.w_floats = l.patch_layout ? (size_t)pf : (size_t)a.K * (a.C / a.groups) * a.R * a.S;
+    return l;
+}
+
+hipError_t launch_conv2d_pack(const ConvArgs& a, float* pack, hipStream_t stream)
+{
+    const ConvPackLayout l = conv2d_pack_layout(a);
+    if (a.gamma) {
+        hipError_t e = launch_kernel(conv_pack_bn_kernel, dim3((unsigned)((a.K + 255) / 256)), dim3(256), 0, stream, a.gamma,
+                                     a.beta, a.mean, a.var, a.eps, pack, a.K);
+        if (e != hipSuccess) return e;
+    }
+    float* wout = pack + l.ss_floats;
+    const int64_t total = (int64_t)l.w_floats;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (!l.patch_layout) return launch_kernel(conv_pack_copy_kernel, grid, dim3(256), 0, stream, a.w, wout, total);
+    ConvArgs b = a;
+    b.x = nullptr;
+    b.w = nullptr;
+    IgemmPlan p;
+    plan_igemm(b, &p);
+    int bn = 0, ck = 0;
+    packed_floats(b, p, &bn, &ck);
+    return launch_kernel(conv_pack_patch_kernel, grid, dim3(256), 0, stream, a.w, wout, a.K, a.C, bn, ck, total);
 }
 
 hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault)

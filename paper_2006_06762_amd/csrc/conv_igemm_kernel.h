@@ -73,14 +73,18 @@ struct Geom {
     // rectangle of (tiles_m / xcd_m) x (tiles_n / xcd_n) tiles that one XCD's L2 serves
     int tiles_m, tiles_n, xcd_m, xcd_n;
     uint32_t x_bytes, w_bytes;   // extents of the x view and of w, for the buffer descriptors
+    uint32_t wpack_bytes;        // extent of the packed weights: tiles_n * chunks * BN * (KC + 2) floats
     FastDiv d_sub_n;            // divisor tiles_n / xcd_n
 };
 
 
 constexpr int kMaxUnits = 8;
 
+// PACKED: the weights come from a pack made by conv_pack_patch_kernel, in which the LDS image of
+// every (channel tile, chunk) is one contiguous run: staging them is a straight copy in 16-byte
+// units, and the batch-norm scale and shift are read, not computed.
 template <int WM_BLK, int WN_BLK, int WAVES_M, int WAVES_N, int KSPLIT, int R_, int S_, int CPH, int XU,
-          int RSL_T, int P_T>
+          int RSL_T, int P_T, bool PACKED>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT)
 void conv_igemm_kernel(const ConvArgs p, const Geom g)
 {
@@ -93,7 +97,9 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     constexpr int STEPS = CPH * RS9;      // MFMA k-steps per chunk (all waves of a tile together)
     constexpr int SPW = STEPS / KSPLIT;   // k-steps per chunk of one wave
     constexpr int WQ = KC / 4;
-    constexpr int WU = (BN * WQ + NT - 1) / NT;
+    constexpr int PU = BN * WS / 4;       // 16-byte units of a packed chunk image
+    static_assert((BN * WS) % 4 == 0, "a chunk image is a whole number of 16-byte units");
+    constexpr int WU = ((PACKED ? PU : BN * WQ) + NT - 1) / NT;
     constexpr int NBLK = WM_BLK * WN_BLK; // MFMAs per k-step of one wave
     constexpr int SLOTS = SPW * NBLK;     // MFMAs per chunk of one wave = issue slots for staging
     constexpr int NSIDE = XU + WU;        // staging units per thread and chunk
@@ -164,13 +170,21 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     // duplicate earlier units, channels past K re-read the last valid channel (their products
     // land in accumulator columns that are never stored)
     uint32_t woff[WU], wlds[WU];
+    const int nchunks = p.C / CK;
 #pragma unroll
     for (int i = 0; i < WU; ++i) {
-        const int u = (tid + i * NT) % (BN * WQ);
-        const int co = u / WQ, kq = u - co * WQ;
-        const int gco = co0 + co < p.K ? co0 + co : p.K - 1;
-        woff[i] = 4u * (uint32_t)(gco * (p.C * RS9) + 4 * kq);
-        wlds[i] = 4u * (uint32_t)(2 * patch_sz + co * WS + 4 * kq);
+        if (PACKED) {
+            // unit u of the chunk image goes to unit u of the LDS buffer
+            const int u = (tid + i * NT) % PU;
+            woff[i] = 4u * (uint32_t)(tile_n * nchunks * (BN * WS) + 4 * u);
+            wlds[i] = 4u * (uint32_t)(2 * patch_sz + 4 * u);
+        } else {
+            const int u = (tid + i * NT) % (BN * WQ);
+            const int co = u / WQ, kq = u - co * WQ;
+            const int gco = co0 + co < p.K ? co0 + co : p.K - 1;
+            woff[i] = 4u * (uint32_t)(gco * (p.C * RS9) + 4 * kq);
+            wlds[i] = 4u * (uint32_t)(2 * patch_sz + co * WS + 4 * kq);
+        }
     }
 
     // ---- per-lane operand addresses in LDS, bytes (the wave's share of the k-steps is folded in)
@@ -200,15 +214,14 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
     f32x4 rx[XU], rw[WU];
-    const int nchunks = p.C / CK;
 
     // staging unit j: global -> registers.  Buffer loads: the descriptor (base, extent) sits in
     // scalar registers for the whole kernel, the lane supplies a 32-bit byte offset and the chunk
     // a scalar one, so a load needs no vector ALU work for its address.
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t wrsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.w), 0, (int)g.w_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(PACKED ? p.wpack : p.w), 0, (int)(PACKED ? g.wpack_bytes : g.w_bytes), 0x00020000);
     auto side_load = [&](int j, uint32_t xchunk_b, uint32_t wchunk_b) {
         if (j < XU)
             rx[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)xoff[j], (int)xchunk_b, 0));
@@ -221,10 +234,15 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             if (xvalid[j]) *reinterpret_cast<f32x4*>(lds + xlds[j] + xbuf_b) = rx[j];
         } else {
             const f32x4 v = rw[j - XU];
-            f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
-            f32x2* dst = reinterpret_cast<f32x2*>(lds + wlds[j - XU] + wbuf_b);
-            dst[0] = lo;
-            dst[1] = hi;
+            if (PACKED) {
+                *reinterpret_cast<f32x4*>(lds + wlds[j - XU] + wbuf_b) = v;
+            } else {
+                // a channel's row in LDS starts 8-byte aligned only (stride KC + 2)
+                f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+                f32x2* dst = reinterpret_cast<f32x2*>(lds + wlds[j - XU] + wbuf_b);
+                dst[0] = lo;
+                dst[1] = hi;
+            }
         }
     };
 
@@ -243,7 +261,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         // the chunk after the last one is the last one again: loaded and stored, never read
         const int cn = cc + 1 < nchunks ? cc + 1 : cc;
         const uint32_t xb = 4u * (uint32_t)cn * (uint32_t)(CK * p.xs[1]);     // byte offset of the chunk
-        const uint32_t wb = 4u * (uint32_t)cn * (uint32_t)KC;
+        const uint32_t wb = 4u * (uint32_t)cn * (uint32_t)(PACKED ? BN * WS : KC);
         const int rd_a = 4 * buf * patch_sz, rd_b = 4 * buf * WTS_SZ;
         const int st_a = 4 * (buf ^ 1) * patch_sz, st_b = 4 * (buf ^ 1) * WTS_SZ;
 
@@ -328,7 +346,10 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         const int co = co0 + (wave_n * WN_BLK + nb) * 32 + r32;
         if (co >= p.K) continue;
         float scale = 1.f, shift = 0.f;
-        if (p.gamma) {
+        if (p.gamma && p.scale_shift) {         // folded ahead of time (pre-packed call)
+            scale = p.scale_shift[co];
+            shift = p.scale_shift[p.K + co];
+        } else if (p.gamma) {
             scale = p.gamma[co] / sqrtf(p.var[co] + p.eps);
             shift = p.beta[co] - p.mean[co] * scale;
         }
@@ -398,6 +419,12 @@ struct Variant {
     static constexpr int SLOTS = (CPH * R_ * S_ / KSPLIT) * WM_BLK * WN_BLK;
     static constexpr int kMaxXU = (SLOTS / 2 - WU) < kMaxUnits ? (SLOTS / 2 - WU) : kMaxUnits;
 
+    // Floats of the packed weights: per channel tile and chunk one LDS image of BN rows of KC + 2.
+    static int64_t packed_floats(const ConvArgs& a)
+    {
+        return (int64_t)((a.K + BN - 1) / BN) * (a.C / CK) * BN * WS;
+    }
+
     // Fills the geometry; false if this variant cannot run the problem.
     static bool plan(const ConvArgs& a, Geom* g, size_t* lds_bytes)
     {
@@ -428,6 +455,7 @@ struct Variant {
         g->x_bytes = (uint32_t)(4 * ((int64_t)(a.N - 1) * a.xs[0] + (int64_t)(a.C - 1) * a.xs[1] +
                                      (int64_t)(a.H - 1) * a.xs[2] + a.W));
         g->w_bytes = (uint32_t)(4 * (int64_t)a.K * a.C * a.R * a.S);
+        g->wpack_bytes = (uint32_t)(4 * packed_floats(a));
         // XCD-aware tile mapping: split the tile grid 8 ways (xcd_m x xcd_n) so that the bytes one
         // XCD has to pull through its L2 (its share of x plus its share of w) are smallest
         g->tiles_m = (g->Mtot + BM - 1) / BM;
@@ -460,7 +488,14 @@ struct Variant {
     template <int XU, int RSL_T, int P_T>
     static hipError_t launch_inst(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
     {
-        auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T>;
+        return a.wpack ? launch_as<XU, RSL_T, P_T, true>(a, g, lds_bytes, stream)
+                       : launch_as<XU, RSL_T, P_T, false>(a, g, lds_bytes, stream);
+    }
+
+    template <int XU, int RSL_T, int P_T, bool PACKED>
+    static hipError_t launch_as(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    {
+        auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T, PACKED>;
         if (lds_bytes > 64 * 1024) {
             static LdsLimit granted;
             hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);

@@ -156,6 +156,46 @@ def test_conv2d_noalloc_validation():
     assert int(re.search(r"ANR_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", text).group(1)) << 20 == B.STATIC_SCRATCH_BYTES
 
 
+def test_packed_weights_size_and_validation():
+    lib = B.raw()
+    n = ctypes.c_size_t(0)
+    # patch-kernel plan: scale/shift block (2K floats rounded up to 64) + per channel tile and chunk an
+    # LDS image of 32 rows x (16 channels x 9 taps + 2) floats for the 28x28 ConvLayer shape
+    d = B.conv_desc((16, 128, 28, 28), 128, 3, 3, (1, 1), (1, 1))
+    assert B.conv2d_packed_size(d) == 4 * (256 + 4 * 8 * 32 * (16 * 9 + 2))
+    # the stride-2 layer: chunks of 8 channels, 16 channel tiles of 32
+    d2 = B.conv_desc((16, 256, 28, 28), 512, 3, 3, (2, 2), (1, 1))
+    assert B.conv2d_packed_size(d2) == 4 * (1024 + 16 * 32 * 32 * (8 * 9 + 2))
+    # any other plan keeps OIHW order
+    d3 = B.conv_desc((1, 3, 224, 224), 64, 7, 7, (2, 2), (3, 3))
+    assert B.conv2d_packed_size(d3) == 4 * (128 + 64 * 3 * 49)
+    # the route is part of the plan
+    d4 = B.conv_desc((16, 128, 28, 28), 128, 3, 3, (1, 1), (1, 1), route=B.ANR_CONV_ROUTE_GENERAL)
+    assert B.conv2d_packed_size(d4) == 4 * (256 + 128 * 128 * 9)
+    assert lib.anr_conv2d_packed_size(ctypes.byref(d), None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d_packed_size(None, ctypes.byref(n)) == B.ANR_ERR_NULL
+    need = B.conv2d_packed_size(d)
+    f = ctypes.c_float(1e-5)
+    pack = ctypes.c_void_p(0x10000)
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), None, None, None, None, None, f, pack, need, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), DUMMY, None, None, None, None, f, None, need, None) == B.ANR_ERR_NULL
+    # batch-norm vectors: all four or none
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), DUMMY, DUMMY, None, None, None, f, pack, need, None) == B.ANR_ERR_NULL
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, ctypes.c_float(float("inf")),
+                                       pack, need, None) == B.ANR_ERR_INVALID_ARG
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), DUMMY, None, None, None, None, f, pack, need - 1,
+                                       None) == B.ANR_ERR_WORKSPACE
+    assert lib.anr_conv2d_pack_weights(ctypes.byref(d), DUMMY, None, None, None, None, f, ctypes.c_void_p(0x10010), need,
+                                       None) == B.ANR_ERR_INVALID_ARG          # pack not 256-byte aligned
+    for fn in (lib.anr_conv2d_packed, lib.anr_conv_bn_relu_packed):
+        assert fn(ctypes.byref(d), None, pack, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+        assert fn(ctypes.byref(d), DUMMY, None, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+        assert fn(ctypes.byref(d), DUMMY, ctypes.c_void_p(0x10010), DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+        assert fn(None, DUMMY, pack, DUMMY, None, 0, None) == B.ANR_ERR_NULL
+        # a pack in the patch kernel's order and an x that kernel cannot read
+        assert fn(ctypes.byref(d), ctypes.c_void_p(0x1004), pack, DUMMY, None, 0, None) == B.ANR_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("fn", ["anr_tbg", "anr_tbs"])
 def test_tbg_validation(fn):
     lib = B.raw()

@@ -219,6 +219,95 @@ def test_conv2d_small(anr, conv_route, shape, ints):
     assert_parity(y, oracle.conv2d(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
 
 
+# ------------------------------------------------------------------ pre-packed weights
+@pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
+def test_conv2d_packed_configs(anr, name):
+    """The benchmark convolutions with pre-packed weights: within the bar of the oracle, and bit for
+    bit what the unpacked call gives (same products, same order)."""
+    cfg = I.config_inputs(name)
+    s = cfg["shape"]
+    xd, wd = dev(cfg["x"]), dev(cfg["w"])
+    d, pack = anr.conv2d_pack_weights((s.N, s.C, s.H, s.W), wd, s.stride, s.pad)
+    assert anr.conv2d_route(d).kernel == anr.ANR_CONV_KERNEL_PATCH
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d_packed(d, xd, pack, y)
+    check_guard(buf)
+    assert_parity(y, oracle.conv2d(cfg["x"], cfg["w"], s.stride, s.pad), what=name + " packed")
+    y2 = torch.empty_like(y)
+    anr.conv2d(xd, wd, y2, s.stride, s.pad)
+    assert torch.equal(y, y2), "packed and unpacked results differ"
+
+
+def test_conv_bn_relu_packed_config(anr):
+    cfg = I.config_inputs("ConvLayer")
+    s = cfg["shape"]
+    xd, wd = dev(cfg["x"]), dev(cfg["w"])
+    bn = [dev(cfg[k]) for k in ("gamma", "beta", "mean", "var")]
+    d, pack = anr.conv2d_pack_weights((s.N, s.C, s.H, s.W), wd, s.stride, s.pad, bn=bn, eps=cfg["eps"])
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv_bn_relu_packed(d, xd, pack, y)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu(cfg["x"], cfg["w"], cfg["gamma"], cfg["beta"], cfg["mean"], cfg["var"], cfg["eps"],
+                              s.stride, s.pad)
+    assert_parity(y, ref, what="ConvLayer packed")
+    y2 = torch.empty_like(y)
+    anr.conv_bn_relu(xd, wd, *bn, cfg["eps"], y2, s.stride, s.pad)
+    assert torch.equal(y, y2), "packed and unpacked results differ"
+    # the same pack without the fused epilogue is the plain convolution
+    anr.conv2d_packed(d, xd, pack, y)
+    assert_parity(y, oracle.conv2d(cfg["x"], cfg["w"], s.stride, s.pad), what="ConvLayer pack, plain conv")
+
+
+PACKED_SHAPES = [
+    (I.ConvShape(3, 16, 20, 24, 40, 3, 3, (1, 1), (1, 1)), 1),        # patch kernel, channel tile past K, ragged pixel tile
+    (I.ConvShape(2, 24, 17, 12, 70, 3, 3, (2, 2), (1, 1)), 1),        # patch kernel, stride 2, three chunks
+    (I.ConvShape(8, 32, 28, 28, 32, 3, 3, (1, 1), (1, 1)), 0),        # library's choice
+    (I.ConvShape(1, 64, 14, 14, 96, 3, 3, (1, 1), (1, 1)), 0),        # general kernel, split reduction
+    (I.ConvShape(2, 3, 30, 30, 16, 7, 7, (2, 2), (3, 3)), 0),         # 7x7
+    (I.ConvShape(2, 32, 9, 9, 24, 1, 1, (1, 1), (0, 0)), 0),          # 1x1
+    (I.ConvShape(2, 16, 14, 14, 24, 3, 3, (1, 1), (2, 2), (2, 2), 4), 0),   # grouped, dilated
+]
+
+
+@pytest.mark.parametrize("shape,route", PACKED_SHAPES, ids=str)
+def test_conv2d_packed_small(anr, shape, route):
+    """Integer-valued inputs: the packed call equals the oracle bit for bit, with and without the
+    fused batch norm + ReLU, whatever kernel the descriptor is planned for."""
+    s = shape
+    x, w = I.conv_inputs(s, 1400, ints=True)
+    xd, wd = dev(x), dev(w)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 1401)
+    bn = [dev(v) for v in (gamma, beta, mean, var)]
+    d, pack = anr.conv2d_pack_weights((s.N, s.C, s.H, s.W), wd, s.stride, s.pad, bn=bn, eps=I.BN_EPS, dil=s.dil,
+                                      groups=s.groups, route=route)
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d_packed(d, xd, pack, y)
+    check_guard(buf)
+    assert_parity(y, oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups), exact=True, what="packed %s" % (s,))
+    y2 = torch.empty_like(y)
+    anr.conv_bn_relu_packed(d, xd, pack, y)
+    anr.conv_bn_relu(xd, wd, *bn, I.BN_EPS, y2, s.stride, s.pad, dil=s.dil, groups=s.groups, route=route)
+    assert torch.equal(y, y2), "packed and unpacked ConvLayer differ"
+    ref = oracle.conv_bn_relu_general(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad, s.dil, s.groups)
+    assert_parity(y, ref, what="packed ConvLayer %s" % (s,))
+
+
+def test_conv2d_packed_refuses_an_input_the_pack_was_not_planned_for(anr):
+    """A pack in the patch kernel's order cannot serve a view of x that kernel cannot read."""
+    import ctypes
+    s = I.ConvShape(8, 16, 56, 56, 64, 3, 3, (1, 1), (1, 1))
+    x, w = I.conv_inputs(s, 1410, ints=True)
+    d, pack = anr.conv2d_pack_weights((s.N, s.C, s.H, s.W), dev(w), s.stride, s.pad)
+    assert anr.conv2d_route(d).kernel == anr.ANR_CONV_KERNEL_PATCH
+    xbuf = torch.zeros((x.size + 1,), device="cuda")
+    xbuf[1:] = dev(x).reshape(-1)
+    xv = xbuf[1:].view(*x.shape)                       # 4-byte aligned only
+    y = torch.empty((s.N, s.K, s.OH, s.OW), device="cuda")
+    st = anr.raw().anr_conv2d_packed(ctypes.byref(d), ctypes.c_void_p(xv.data_ptr()), ctypes.c_void_p(pack.data_ptr()),
+                                     ctypes.c_void_p(y.data_ptr()), None, 0, None)
+    assert st == anr.ANR_ERR_INVALID_ARG
+
+
 def test_conv2d_split_k_workspace(anr):
     """A split-K shape with the caller's own workspace, twice: the partial tiles are summed in
     a fixed order, so both runs agree bit for bit; too small a workspace is an error."""
