@@ -277,7 +277,12 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* out, int64_t r
 // of four stages each (512^3) the phases took 1.6 + 2.9 + 0.35 + 0.45 us; sixteen waves of one
 // stage put four waves on every SIMD, so one wave's staging overlaps another's MFMAs and each
 // wave issues 8 loads instead of 32: 6.5 -> 5.8 us cold.  Weaving the later stages' loads
-// between the MFMAs of the four-stage form had changed nothing.
+// between the MFMAs of the four-stage form had changed nothing.  Also measured and dropped: A
+// brought to LDS by direct-to-LDS loads (unit q of row r on slot q ^ (r % 8), so the rows can sit
+// 128 bytes apart without bank conflicts) and the B operand of every k-step loaded straight into
+// its register (for a fixed k the 32 lanes of a half-wave read one whole line of B): no LDS store
+// and no strided LDS read is left, yet 6.0 against 5.6 us cold -- sixteen 4-byte loads per lane
+// are sixteen more trips through the address unit than the four 16-byte loads they replace.
 
 constexpr int kKsLd = 36;                       // LDS row stride (floats) of a 32-wide stage
 constexpr int kKsStage = 2 * 32 * kKsLd;        // floats per stage: A block then B block
