@@ -374,6 +374,10 @@ def main():
                     help="profiling aid: every launch of the run reads buffers that are not in the caches (24 sets in "
                          "rotation everywhere, no warm or eager per-operator timing), so that a kernel trace of the "
                          "run holds cold launches only")
+    ap.add_argument("--no-per-op", action="store_true",
+                    help="profiling aid: time the step only (no per-operator timing loops, no roofline): with --only, "
+                         "--cold-only and --eager every launch of the run is one cold launch of that operator's kernel, "
+                         "issued on its own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run 10 plain device copies of 256 MiB (known HBM traffic for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -495,6 +499,8 @@ def main():
     # per-operator launch times
     per_op = []
     measured = tuple(names) + (EXTRA_OPS if args.only is None else ())
+    if args.no_per_op:
+        measured = ()
     for n in measured:
         flops, nbytes, bound = table[n]
         reps = 200
@@ -518,6 +524,12 @@ def main():
         rec["in_step"] = n in names
         per_op.append(rec)
 
+    if not per_op:
+        print(json.dumps({"metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": ms_per_step, "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": "only " + str(args.only), "buffer_sets_rotated": rot,
+                                     "timed_steps": args.steps * rounds}}))
+        return
     by = {r["op"]: r for r in per_op}
     dom = by.get("C2D_S2") or per_op[0]
     # HBM traffic per launch is a stored figure (two rocprofv3 --pmc runs, kept under profiles/),

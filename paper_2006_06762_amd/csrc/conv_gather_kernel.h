@@ -90,7 +90,9 @@ __device__ __forceinline__ void store_quad(const ConvArgs& p, const Plan& g, int
     store_quad_plain(p, g, mq, co, v);
 }
 
-// The four values as they are: pixels mq .. mq+3 of output channel co.
+// The four values as they are: pixels mq .. mq+3 of output channel co.  (Ordinary stores: storing
+// the 256-byte runs of store_tile_runs non-temporally changed none of the Appendix C layers by
+// more than the run-to-run spread.)
 __device__ __forceinline__ void store_quad_plain(const ConvArgs& p, const Plan& g, int mq, int co, f32x4 v)
 {
     if (g.vec_store) {
