@@ -286,10 +286,14 @@ def shape_list(anr, I, torch):
                 torch.cuda.synchronize()
                 warm = time_graph(torch, lambda i: run(sets[0]), 2 * nsets)
                 cold = time_graph(torch, lambda i: run(sets[i % nsets]), 2 * nsets)
+                # the shape's own roofline: the larger of its matrix time and its traffic time
+                t_mfma, t_hbm = flops / PEAK_MFMA_F32_TFLOPS / 1e6, nbytes / PEAK_HBM_GBS / 1e3     # microseconds
                 rows.append({"op": op, "shape": list(fields), "batch": batch, "us_warm": warm, "us_cold": cold,
                              "tflops_cold": flops / cold / 1e6, "gbs_cold": nbytes / cold / 1e3,
                              "frac_mfma_peak_cold": flops / cold / 1e6 / PEAK_MFMA_F32_TFLOPS,
-                             "frac_hbm_peak_cold": nbytes / cold / 1e3 / PEAK_HBM_GBS, "buffer_sets": nsets})
+                             "frac_hbm_peak_cold": nbytes / cold / 1e3 / PEAK_HBM_GBS, "buffer_sets": nsets,
+                             "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                             "roofline_us": max(t_mfma, t_hbm), "frac_own_roofline_cold": max(t_mfma, t_hbm) / cold})
                 del sets
     return rows
 
