@@ -277,7 +277,8 @@ enum {
     ANR_CONV_KERNEL_TAPS = 2,      /* 3x3 / 1x1 gather kernel with compile-time taps              */
     ANR_CONV_KERNEL_BIGTAPS = 3,   /* 5x5 / 7x7 gather kernel, one channel per chunk              */
     ANR_CONV_KERNEL_GATHER = 4,    /* any-geometry gather kernel                                  */
-    ANR_CONV_KERNEL_DIRECT = 5     /* one thread per output (extents beyond 32-bit offsets)       */
+    ANR_CONV_KERNEL_DIRECT = 5,    /* one thread per output (extents beyond 32-bit offsets)       */
+    ANR_CONV_KERNEL_POINTWISE = 6  /* streaming 1x1 kernel for layers with few channels           */
 };
 typedef struct {
     int32_t kernel;                /* ANR_CONV_KERNEL_*                                           */

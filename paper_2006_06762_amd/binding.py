@@ -59,7 +59,7 @@ class ConvRoute(ctypes.Structure):
 
 ANR_CONV_ROUTE_AUTO, ANR_CONV_ROUTE_PATCH, ANR_CONV_ROUTE_GENERAL = 0, 1, 2
 ANR_CONV_KERNEL_PATCH, ANR_CONV_KERNEL_TAPS, ANR_CONV_KERNEL_BIGTAPS, ANR_CONV_KERNEL_GATHER, \
-    ANR_CONV_KERNEL_DIRECT = 1, 2, 3, 4, 5
+    ANR_CONV_KERNEL_DIRECT, ANR_CONV_KERNEL_POINTWISE = 1, 2, 3, 4, 5, 6
 
 
 class NrmDesc(ctypes.Structure):

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libanr.so")
 
-SOURCES = ["api.cpp", "gemm.hip", "tbg.hip", "conv_direct.hip", "conv_igemm.hip", "conv_gather.hip", "dwconv.hip", "nrm.hip", "static_scratch.hip"]
+SOURCES = ["api.cpp", "gemm.hip", "tbg.hip", "conv_direct.hip", "conv_igemm.hip", "conv_gather.hip", "conv_pointwise.hip", "dwconv.hip", "nrm.hip", "static_scratch.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

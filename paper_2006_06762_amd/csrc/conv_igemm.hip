@@ -197,7 +197,7 @@ bool describe_conv2d_igemm(const ConvArgs& a, ConvRoute* r)
 
 void describe_conv2d(const ConvArgs& a, ConvRoute* r)
 {
-    if (describe_conv2d_igemm(a, r) || describe_conv2d_gather(a, r)) return;
+    if (describe_conv2d_igemm(a, r) || describe_conv2d_pointwise(a, r) || describe_conv2d_gather(a, r)) return;
     *r = ConvRoute{5, 0, 0, 1, 1, 0, 0};
 }
 
@@ -211,7 +211,10 @@ hipError_t launch_conv2d_igemm(const ConvArgs& a, hipStream_t stream, bool* take
 
 size_t conv2d_workspace_bytes(const ConvArgs& a)
 {
-    return conv2d_igemm_takes(a) ? 0 : conv2d_gather_workspace_bytes(a);
+    if (conv2d_igemm_takes(a)) return 0;
+    ConvRoute r;
+    if (describe_conv2d_pointwise(a, &r)) return 0;
+    return conv2d_gather_workspace_bytes(a);
 }
 
 ConvPackLayout conv2d_pack_layout(const ConvArgs& a)
@@ -259,6 +262,8 @@ hipError_t launch_conv2d(const ConvArgs& a, hipStream_t stream, int* ws_fault)
     *ws_fault = 0;
     bool taken = false;
     hipError_t err = launch_conv2d_igemm(a, stream, &taken);
+    if (taken || err != hipSuccess) return err;
+    err = launch_conv2d_pointwise(a, stream, &taken);
     if (taken || err != hipSuccess) return err;
     err = launch_conv2d_gather(a, stream, &taken, ws_fault);
     if (taken || err != hipSuccess) return err;

@@ -21,14 +21,18 @@ bool conv2d_igemm_takes(const ConvArgs& a);
 hipError_t launch_conv2d_gather(const ConvArgs& a, hipStream_t stream, bool* taken, int* ws_fault);
 size_t conv2d_gather_workspace_bytes(const ConvArgs& a);
 
+// Streaming kernel for pointwise layers with few channels (conv_pointwise_kernel.h); same contract.
+hipError_t launch_conv2d_pointwise(const ConvArgs& a, hipStream_t stream, bool* taken);
+
 // What a launch would do, for introspection (nothing is launched).
 struct ConvRoute {
-    int kernel;          // 1 patch-staging, 2 taps, 3 bigtaps, 4 gather, 5 direct (the public ANR_CONV_KERNEL_* values)
+    int kernel;          // 1 patch-staging, 2 taps, 3 bigtaps, 4 gather, 5 direct, 6 pointwise stream (the public ANR_CONV_KERNEL_* values)
     int tile_m, tile_n, ksplit, wave_groups, work_groups;
     size_t workspace_bytes;
 };
 bool describe_conv2d_igemm(const ConvArgs& a, ConvRoute* r);
 bool describe_conv2d_gather(const ConvArgs& a, ConvRoute* r);
+bool describe_conv2d_pointwise(const ConvArgs& a, ConvRoute* r);
 void describe_conv2d(const ConvArgs& a, ConvRoute* r);
 
 // Register-sliding 3x3 / stride 1 / pad 1 depthwise kernel; same contract.

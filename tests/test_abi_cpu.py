@@ -327,11 +327,22 @@ def test_conv_route_by_kernel_size_and_channels():
     assert r.kernel == K.ANR_CONV_KERNEL_TAPS and r.ksplit > 1 and r.workspace_bytes > 0
     assert r.workspace_bytes == K.workspace_size(K.ANR_OP_CONV2D, d)
     # 14x14 and 7x7 maps (width not a multiple of 4), pointwise layers: compile-time taps, 64x64 tiles
-    for shape, Kout, R, pad in [((16, 256, 14, 14), 256, 3, 1), ((16, 512, 7, 7), 512, 3, 1), ((16, 64, 56, 56), 64, 1, 0),
+    for shape, Kout, R, pad in [((16, 256, 14, 14), 256, 3, 1), ((16, 512, 7, 7), 512, 3, 1), ((16, 64, 56, 56), 256, 1, 0),
                                 ((16, 1024, 14, 14), 256, 1, 0)]:
         d, r = route(shape, Kout, R, 1, pad)
         assert r.kernel == K.ANR_CONV_KERNEL_TAPS and (r.tile_m, r.tile_n) == (64, 64)
         assert r.workspace_bytes == K.workspace_size(K.ANR_OP_CONV2D, d)
+    # pointwise layers with few channels on dense images: the streaming kernel (no workspace); not with
+    # more channels, groups, a stride, too few tiles, or when the general family is ruled out by route 1
+    d, r = route((16, 64, 56, 56), 64, 1)
+    assert r.kernel == K.ANR_CONV_KERNEL_POINTWISE and r.work_groups == 16 * 49 and r.workspace_bytes == 0
+    assert K.workspace_size(K.ANR_OP_CONV2D, d) == 0
+    assert route((16, 128, 28, 28), 100, 1)[1].kernel == K.ANR_CONV_KERNEL_POINTWISE
+    assert route((16, 256, 28, 28), 64, 1)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((16, 64, 56, 56), 64, 1, stride=2)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((1, 64, 56, 56), 64, 1)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((16, 64, 56, 56), 64, 1, groups=4)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((16, 64, 56, 56), 64, 1, dil=2)[1].kernel == K.ANR_CONV_KERNEL_POINTWISE      # one tap: dilation is moot
     # 7x7 stem and 5x5: one channel per chunk
     assert route((16, 3, 224, 224), 64, 7, 2, 3)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
     assert route((2, 32, 28, 28), 64, 5, 1, 2)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS

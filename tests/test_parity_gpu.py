@@ -219,6 +219,47 @@ def test_conv2d_small(anr, conv_route, shape, ints):
     assert_parity(y, oracle.conv2d(x, w, shape.stride, shape.pad), exact=ints, what=str(shape))
 
 
+# ------------------------------------------------------------------ streaming pointwise kernel
+POINTWISE_SHAPES = [
+    I.ConvShape(16, 64, 56, 56, 64, 1, 1, (1, 1), (0, 0)),       # the Appendix C layer
+    I.ConvShape(18, 32, 30, 30, 24, 1, 1, (1, 1), (0, 0)),       # 900 pixels: ragged pixel tile, channels past K
+    I.ConvShape(10, 96, 26, 34, 100, 1, 1, (1, 1), (0, 0)),      # two channel tiles, the second ragged
+    I.ConvShape(32, 128, 14, 14, 128, 1, 1, (1, 1), (0, 0)),     # 196 pixels: three whole tiles and four pixels
+]
+
+
+@pytest.mark.parametrize("shape", POINTWISE_SHAPES, ids=str)
+def test_conv2d_pointwise_stream(anr, shape):
+    """1x1 layers with few channels run the streaming kernel: integer values bit for bit, then the
+    ConvLayer epilogue within the bar, on dense tensors and on images spaced apart in x and y."""
+    s = shape
+    d = anr.conv_desc((s.N, s.C, s.H, s.W), s.K, 1, 1)
+    assert anr.conv2d_route(d).kernel == anr.ANR_CONV_KERNEL_POINTWISE
+    x, w = I.conv_inputs(s, 1500, ints=True)
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+    check_guard(buf)
+    ref = oracle.conv2d(x, w, s.stride, s.pad)
+    assert_parity(y, ref, exact=True, what="pointwise %s" % (s,))
+    # images 8 floats further apart than dense, in x and in y
+    xw = torch.zeros((s.N, s.C * s.H * s.W + 8), device="cuda")
+    xw[:, :s.C * s.H * s.W] = dev(x).reshape(s.N, -1)
+    yw = torch.full((s.N, s.K * s.OH * s.OW + 8), CANARY, device="cuda")
+    xv = xw[:, :s.C * s.H * s.W].view(s.N, s.C, s.H, s.W)
+    yv = yw[:, :s.K * s.OH * s.OW].view(s.N, s.K, s.OH, s.OW)
+    anr.conv2d(xv, dev(w), yv, s.stride, s.pad)
+    assert_parity(yv.contiguous(), ref, exact=True, what="pointwise, spaced images %s" % (s,))
+    assert bool((yw[:, s.K * s.OH * s.OW:] == CANARY).all()), "store between the images"
+    x, w = I.conv_inputs(s, 1501)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 1502)
+    w = (w * 4).astype(np.float32)
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad)
+    check_guard(buf)
+    assert_parity(y, oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad), what="pointwise ConvLayer %s" % (s,))
+    got = y.cpu().numpy()
+    assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
+
+
 # ------------------------------------------------------------------ pre-packed weights
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
 def test_conv2d_packed_configs(anr, name):
@@ -265,6 +306,7 @@ PACKED_SHAPES = [
     (I.ConvShape(1, 64, 14, 14, 96, 3, 3, (1, 1), (1, 1)), 0),        # general kernel, split reduction
     (I.ConvShape(2, 3, 30, 30, 16, 7, 7, (2, 2), (3, 3)), 0),         # 7x7
     (I.ConvShape(2, 32, 9, 9, 24, 1, 1, (1, 1), (0, 0)), 0),          # 1x1
+    (I.ConvShape(8, 64, 48, 48, 64, 1, 1, (1, 1), (0, 0)), 0),        # 1x1, streaming kernel
     (I.ConvShape(2, 16, 14, 14, 24, 3, 3, (1, 1), (2, 2), (2, 2), 4), 0),   # grouped, dilated
 ]
 
