@@ -889,6 +889,23 @@ def test_conv2d_random_geometries_tap_kernels(anr):
         assert_parity(y, ref, exact=True, what="random tap-kernel conv %d %s" % (i, s))
 
 
+def test_conv2d_large_batch_without_split_keeps_the_mfma_kernel(anr):
+    """A VGG-style stem at batch 24 (3 channels rule out the tap kernels; 77 M outputs): the plan does
+    not split the reduction, so the cap on the split-K workspace must not push it to the
+    one-thread-per-output kernel.  Checked on the first and the last image (an image's outputs depend
+    on that image alone)."""
+    s = I.ConvShape(24, 3, 224, 224, 64, 3, 3, (1, 1), (1, 1))
+    d = anr.conv_desc((s.N, s.C, s.H, s.W), s.K, 3, 3, s.stride, s.pad)
+    r = anr.conv2d_route(d)
+    assert r.kernel == anr.ANR_CONV_KERNEL_GATHER and r.ksplit == 1
+    x, w = I.conv_inputs(s, 1600)
+    y = torch.empty((s.N, s.K, s.OH, s.OW), device="cuda")
+    anr.conv2d(dev(x), dev(w), y, s.stride, s.pad)
+    for n in (0, s.N - 1):
+        ref = oracle.conv2d(x[n:n + 1], w, s.stride, s.pad)
+        assert_parity(y[n:n + 1], ref, what="stem at batch 24, image %d" % n)
+
+
 def test_conv2d_wave_groups_share_a_chain(anr):
     """About 200 output tiles with 16 and with 32 chunks each and no split-K: the work-groups of
     the compile-time-tap kernel then run two and four groups of waves that take alternate chunks
