@@ -155,11 +155,11 @@ __global__ __launch_bounds__(64 * WPB) void dwconv3x3s2_kernel(const ConvArgs p,
 // Per-wave timestamps showed the arithmetic, not the traffic, to be what such a kernel adds to a
 // copy: its waves get their data within the same microsecond and then share the vector ALUs.
 // So a round of the wave covers whole rows (RPR = floor(64 / (W/4)) of them, LPR = RPR * W/4
-// lanes): a lane keeps its column for all rounds, the tests for the plane's left and right edge
-// are folded into the lane's copy of the weights once, a zero row in LDS stands in for the row
-// above and below the plane, and with the width known at compile time every LDS and global
-// address of a round is the lane's base plus an instruction immediate: 36 multiply-adds per
-// round and next to nothing else.  (Tried: the neighbouring columns by DPP wave shift instead of
+// lanes): a lane keeps its column for all rounds, so whether it sits at the plane's left or right
+// edge is decided once and costs one select per edge and round; a zero row in LDS stands in for
+// the row above and below the plane; and with the width known at compile time every LDS and
+// global address of a round is the lane's base plus an instruction immediate: 38 multiply-adds
+// and two selects per round and next to nothing else.  (Tried: the neighbouring columns by DPP wave shift instead of
 // 4-byte LDS reads, which fall on 16 banks: 6.9 against 6.3 us, the shifts are vector-ALU work;
 // edge taps under a branch or as predicated reads: 6.7 us; two to eight items per wave with the
 // loads of all of them in flight: 6.7 to 12.8 us, a wave's chain is what counts; starting the
