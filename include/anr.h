@@ -37,8 +37,11 @@
  *   - Thread-safe and re-entrant.  The library reads no environment variable
  *     and no configuration file: what a call does follows from its arguments
  *     alone.  The only state is a thread-local copy of the last HIP launch
- *     error, kept for anr_last_hip_error(), and a once-per-device note that a
- *     kernel's shared-memory limit has been raised (idempotent).
+ *     error, kept for anr_last_hip_error(), and two idempotent per-device
+ *     notes: that a kernel's shared-memory limit has been raised, and the
+ *     address of the static scratch array of anr_conv2d_noalloc (whose
+ *     CONTENTS are shared by all calls of that one entry point on a GPU: see
+ *     there).
  */
 #ifndef ANR_H
 #define ANR_H
