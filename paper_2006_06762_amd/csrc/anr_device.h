@@ -56,6 +56,105 @@ __device__ __forceinline__ f32x4 zero4()
     return z;
 }
 
+// Kernel arguments are read through the scalar cache, and the compiler fetches each where it is
+// first used: a kernel with large argument structs starts with several dependent round trips to
+// memory and nothing else to do meanwhile.  This requests one word of each 64-byte line of the
+// first BYTES bytes of the argument block in one go and waits for them; the compiler's own reads
+// then hit the scalar cache.  The loads and their wait are one asm statement, so the registers
+// they write stay reserved until the data is there.
+template <int BYTES>
+__device__ __forceinline__ void touch_kernel_arguments()
+{
+    constexpr int LINES = (BYTES + 63) / 64;
+    static_assert(LINES >= 1 && LINES <= 8, "one to eight lines");
+    auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t t[8];
+    if constexpr (LINES == 8)
+        asm volatile(
+                     "s_load_dword %0, %8, 0x0\n\t"
+                     "s_load_dword %1, %8, 0x40\n\t"
+                     "s_load_dword %2, %8, 0x80\n\t"
+                     "s_load_dword %3, %8, 0xc0\n\t"
+                     "s_load_dword %4, %8, 0x100\n\t"
+                     "s_load_dword %5, %8, 0x140\n\t"
+                     "s_load_dword %6, %8, 0x180\n\t"
+                     "s_load_dword %7, %8, 0x1c0\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2]), "=&s"(t[3]), "=&s"(t[4]), "=&s"(t[5]), "=&s"(t[6]), "=&s"(t[7])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 7)
+        asm volatile(
+                     "s_load_dword %0, %7, 0x0\n\t"
+                     "s_load_dword %1, %7, 0x40\n\t"
+                     "s_load_dword %2, %7, 0x80\n\t"
+                     "s_load_dword %3, %7, 0xc0\n\t"
+                     "s_load_dword %4, %7, 0x100\n\t"
+                     "s_load_dword %5, %7, 0x140\n\t"
+                     "s_load_dword %6, %7, 0x180\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2]), "=&s"(t[3]), "=&s"(t[4]), "=&s"(t[5]), "=&s"(t[6])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 6)
+        asm volatile(
+                     "s_load_dword %0, %6, 0x0\n\t"
+                     "s_load_dword %1, %6, 0x40\n\t"
+                     "s_load_dword %2, %6, 0x80\n\t"
+                     "s_load_dword %3, %6, 0xc0\n\t"
+                     "s_load_dword %4, %6, 0x100\n\t"
+                     "s_load_dword %5, %6, 0x140\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2]), "=&s"(t[3]), "=&s"(t[4]), "=&s"(t[5])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 5)
+        asm volatile(
+                     "s_load_dword %0, %5, 0x0\n\t"
+                     "s_load_dword %1, %5, 0x40\n\t"
+                     "s_load_dword %2, %5, 0x80\n\t"
+                     "s_load_dword %3, %5, 0xc0\n\t"
+                     "s_load_dword %4, %5, 0x100\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2]), "=&s"(t[3]), "=&s"(t[4])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 4)
+        asm volatile(
+                     "s_load_dword %0, %4, 0x0\n\t"
+                     "s_load_dword %1, %4, 0x40\n\t"
+                     "s_load_dword %2, %4, 0x80\n\t"
+                     "s_load_dword %3, %4, 0xc0\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2]), "=&s"(t[3])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 3)
+        asm volatile(
+                     "s_load_dword %0, %3, 0x0\n\t"
+                     "s_load_dword %1, %3, 0x40\n\t"
+                     "s_load_dword %2, %3, 0x80\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1]), "=&s"(t[2])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 2)
+        asm volatile(
+                     "s_load_dword %0, %2, 0x0\n\t"
+                     "s_load_dword %1, %2, 0x40\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0]), "=&s"(t[1])
+                     : "s"(ka)
+                     : "memory");
+    else if constexpr (LINES == 1)
+        asm volatile(
+                     "s_load_dword %0, %1, 0x0\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(t[0])
+                     : "s"(ka)
+                     : "memory");
+}
+
 // floor(n / d) for 0 <= n < 2^31 as one multiply-high and one shift (Granlund-Montgomery
 // round-up method: mul = ceil(2^(31+l) / d), l = ceil(log2 d), quotient = (n*mul) >> (31+l)).
 struct FastDiv {

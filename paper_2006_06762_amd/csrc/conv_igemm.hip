@@ -10,7 +10,6 @@ using namespace igemm;
 //                       WM WN  wM wN ks  R  S CPH   (tile = 32*WM*wM pixels x 32*WN*wN channels)
 using V224x64 = Variant<7, 1, 1, 2, 2, 3, 3, 4>;   // 4 waves: two 7x1-block tiles, 2-way k split
 using V224x32 = Variant<7, 1, 1, 1, 4, 3, 3, 4>;   // 4 waves share one 7x1-block tile along k
-using V224x32c16 = Variant<7, 1, 1, 1, 4, 3, 3, 8>; // the same tile with chunks of 16 channels (fixed-geometry instantiations only)
 using V128x64 = Variant<2, 2, 2, 1, 2, 3, 3, 4>;   // 4 waves, 2x2 blocks each, 2-way k split
 using V64x64 = Variant<2, 2, 1, 1, 4, 3, 3, 4>;    // 4 waves share one 2x2-block tile along k
 
@@ -32,11 +31,11 @@ void consider(const ConvArgs& a, double* best_cost, int* best, int id, Geom* g, 
 // Instantiations whose LDS geometry is a compile-time constant, one per (tile variant, LDS
 // row stride, LDS plane stride): the shapes of the ResNet-style 3x3 layers this library is
 // tuned on.  Anything else runs the same kernel with run-time strides.
-template <class V, int XU, int RSL_T, int P_T>
+template <class V, int XU, int RSL_T, int P_T, int NBUF>
 bool try_fixed(const ConvArgs& a, const Geom& g, size_t lds, hipStream_t stream, hipError_t* err)
 {
     if (g.RSL != RSL_T || g.P != P_T || V::units_per_thread(g) > XU) return false;
-    *err = V::template launch_fixed<XU, RSL_T, P_T>(a, g, lds, stream);
+    *err = V::template launch_fixed<XU, RSL_T, P_T, NBUF>(a, g, lds, stream);
     return true;
 }
 
@@ -71,7 +70,7 @@ int select_variant(const ConvArgs& a, Geom* g, size_t* lds)
 constexpr int kMinTunedWorkGroups = 112;
 
 struct IgemmPlan {
-    int variant;     // 0 V224x64, 1 V224x32, 2 V128x64, 3 V64x64, 4 V224x32c16; -1: the kernel does not take the call
+    int variant;     // 0 V224x64, 1 V224x32, 2 V128x64, 3 V64x64; -1: the kernel does not take the call
     Geom g;
     size_t lds;
 };
@@ -88,16 +87,6 @@ void plan_igemm(const ConvArgs& a, IgemmPlan* p)
     if (best < 0) return;
     if (a.route != 1 && (int64_t)p->g.tiles_m * p->g.tiles_n < kMinTunedWorkGroups) return;
     p->variant = best;
-    if (best == 1) {
-        // 28x28 maps, stride 1: chunks of 16 channels halve the barriers of the four-way k split
-        Geom g16;
-        size_t lds16 = 0;
-        if (V224x32c16::plan(a, &g16, &lds16) && g16.RSL == 36 && g16.P == 432 && V224x32c16::units_per_thread(g16) <= 6) {
-            p->variant = 4;
-            p->g = g16;
-            p->lds = lds16;
-        }
-    }
 }
 
 hipError_t launch_igemm_plan(const ConvArgs& a, const IgemmPlan& p, hipStream_t stream)
@@ -107,12 +96,11 @@ hipError_t launch_igemm_plan(const ConvArgs& a, const IgemmPlan& p, hipStream_t 
     hipError_t err = hipSuccess;
     switch (p.variant) {
         case 0:
-            if (try_fixed<V224x64, 3, 64, 384>(a, g, lds, stream, &err)) return err;    // 56x56 maps, stride 1
+            if (try_fixed<V224x64, 3, 64, 384, 3>(a, g, lds, stream, &err)) return err;     // 56x56 maps, stride 1
             return V224x64::launch(a, g, lds, stream);
-        case 4: return V224x32c16::launch_fixed<6, 36, 432>(a, g, lds, stream);          // 28x28 maps, stride 1
         case 1:
-            if (try_fixed<V224x32, 6, 36, 432>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 1
-            if (try_fixed<V224x32, 8, 32, 1088>(a, g, lds, stream, &err)) return err;   // 28x28 maps, stride 2
+            if (try_fixed<V224x32, 3, 36, 432, 3>(a, g, lds, stream, &err)) return err;     // 28x28 maps, stride 1
+            if (try_fixed<V224x32, 8, 32, 1088, 3>(a, g, lds, stream, &err)) return err;    // 28x28 maps, stride 2
             return V224x32::launch(a, g, lds, stream);
         case 2: return V128x64::launch(a, g, lds, stream);
         default: return V64x64::launch(a, g, lds, stream);
@@ -127,7 +115,6 @@ int64_t packed_floats(const ConvArgs& a, const IgemmPlan& p, int* bn, int* ck)
         case 1: *bn = V224x32::BN; *ck = V224x32::CK; return V224x32::packed_floats(a);
         case 2: *bn = V128x64::BN; *ck = V128x64::CK; return V128x64::packed_floats(a);
         case 3: *bn = V64x64::BN; *ck = V64x64::CK; return V64x64::packed_floats(a);
-        case 4: *bn = V224x32c16::BN; *ck = V224x32c16::CK; return V224x32c16::packed_floats(a);
         default: *bn = *ck = 0; return 0;
     }
 }

@@ -66,15 +66,20 @@ struct Geom {
     int XC;         // LDS column of input column 0 (multiple of 4)
     int W4;         // W / 4
     int n_units;    // CK * VR * W4 16-byte staging units per chunk
+    int st_ci, st_vr, st_j4;   // the work-group's thread count as (channels, rows, quads) of staging units
+    int row_groups; // > 0: a thread stages one (row, quad) of channels cg, cg + row_groups, ... (cg < row_groups)
+    int slots;      // staging slots a thread needs under the mapping in use
     int vec_store;  // 4 consecutive pixels of a lane are 16 contiguous, aligned bytes of y
     int ohow;       // OH*OW
     FastDiv d_ow, d_oh, d_hv, d_w4, d_perc, d_ohow, d_units;   // divisors OW, OH, HV, W4, VR*W4, OH*OW, n_units
     // work-group id -> tile: ids are dealt round-robin over the 8 XCDs, so id % 8 picks a
     // rectangle of (tiles_m / xcd_m) x (tiles_n / xcd_n) tiles that one XCD's L2 serves
     int tiles_m, tiles_n, xcd_m, xcd_n;
+    int sub_m, sub_n, xcd_n_shift;   // tiles_m / xcd_m, tiles_n / xcd_n, log2(xcd_n)
     uint32_t x_bytes, w_bytes;   // extents of the x view and of w, for the buffer descriptors
     uint32_t wpack_bytes;        // extent of the packed weights: tiles_n * chunks * BN * (KC + 2) floats
     FastDiv d_sub_n;            // divisor tiles_n / xcd_n
+    FastDiv d_tiles_m;
 };
 
 
@@ -84,7 +89,7 @@ constexpr int kMaxUnits = 8;
 // every (channel tile, chunk) is one contiguous run: staging them is a straight copy in 16-byte
 // units, and the batch-norm scale and shift are read, not computed.
 template <int WM_BLK, int WN_BLK, int WAVES_M, int WAVES_N, int KSPLIT, int R_, int S_, int CPH, int XU,
-          int RSL_T, int P_T, bool PACKED>
+          int RSL_T, int P_T, bool PACKED, int NBUF>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT)
 void conv_igemm_kernel(const ConvArgs p, const Geom g)
 {
@@ -117,11 +122,13 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     const int patch_sz = CK * P;                     // floats per patch buffer
     constexpr int WTS_SZ = BN * WS;                  // floats per weight buffer
 
+    static_assert(NBUF == 2 || NBUF == 3, "two staging buffers, or a ring of three");
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    // layout: patch[2][patch_sz], then wts[2][WTS_SZ]
+    // layout: patch[NBUF][patch_sz], then wts[NBUF][WTS_SZ]
     char* const lds = reinterpret_cast<char*>(smem);
 
     const int tid = threadIdx.x;
+    touch_kernel_arguments<sizeof(ConvArgs) + sizeof(Geom)>();
     const int lane = tid & 63, wave = tid >> 6;
     const int r32 = lane & 31, h = lane >> 5;
     const int tile_wave = wave % (WAVES_M * WAVES_N), ks = wave / (WAVES_M * WAVES_N);
@@ -129,15 +136,14 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     int tile_m, tile_n;
     {
         const int w = blockIdx.x;
-        if (g.xcd_m * g.xcd_n == 8) {
+        if (g.xcd_n) {        // the tile grid splits eight ways (xcd_n is a power of two)
             const int xcd = w & 7, slot = w >> 3;
-            const int sub_m = g.tiles_m / g.xcd_m, sub_n = g.tiles_n / g.xcd_n;
             const int lm = g.d_sub_n.div(slot);
-            tile_m = (xcd / g.xcd_n) * sub_m + lm;
-            tile_n = (xcd % g.xcd_n) * sub_n + (slot - lm * sub_n);
+            tile_m = (xcd >> g.xcd_n_shift) * g.sub_m + lm;
+            tile_n = (xcd & (g.xcd_n - 1)) * g.sub_n + (slot - lm * g.sub_n);
         } else {
-            tile_m = w % g.tiles_m;
-            tile_n = w / g.tiles_m;
+            tile_n = g.d_tiles_m.div(w);
+            tile_m = w - tile_n * g.tiles_m;
         }
     }
     const int m0 = tile_m * BM, co0 = tile_n * BN;
@@ -146,26 +152,23 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     const int n_first = g.d_oh.div(g0);
     const int v0 = n_first * g.HV + (g0 - n_first * p.OH) * p.stride_h;
 
-    // ---- staging descriptors: which 16 bytes of x go where in the patch (fixed over chunks).
+    // ---- staging: which 16 bytes of x and w go where in LDS (fixed over chunks), and the loads of
+    //      the first chunk, each issued as soon as its offset is known: everything else the
+    //      kernel sets up (operand addresses, accumulators, zeroed padding) then runs while they
+    //      are in flight.
     //      Every slot of every thread loads something, so that the main loop has no branch
     //      around a load: slots past the end of the patch duplicate an earlier unit (same data
     //      to the same place), units whose row is padding load offset 0 and skip the store
     //      (their rows were zeroed before the first chunk).  Offsets are in bytes, relative to
     //      the first channel of a chunk.
-    uint32_t xoff[XU], xlds[XU];
-    bool xvalid[XU];
-#pragma unroll
-    for (int i = 0; i < XU; ++i) {
-        int u = tid + i * NT;
-        u -= g.d_units.div(u) * g.n_units;
-        const int ci = g.d_perc.div(u), rem = u - ci * (g.VR * g.W4);
-        const int vr = g.d_w4.div(rem), j4 = rem - vr * g.W4;
-        const int v = v0 + vr;
-        const int n = g.d_hv.div(v), ih = v - n * g.HV - p.pad_h;
-        xvalid[i] = n < p.N && ih >= 0 && ih < p.H;
-        xoff[i] = xvalid[i] ? 4u * (uint32_t)(n * p.xs[0] + ci * p.xs[1] + ih * p.xs[2] + 4 * j4) : 0u;
-        xlds[i] = 4u * (uint32_t)(ci * P + vr * RSL + g.XC + 4 * j4);
-    }
+    // Buffer loads: the descriptor (base, extent) sits in scalar registers for the whole kernel, the
+    // lane supplies a 32-bit byte offset and the chunk a scalar one, so a load in the main loop
+    // needs no vector ALU work for its address.
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(PACKED ? p.wpack : p.w), 0, (int)(PACKED ? g.wpack_bytes : g.w_bytes), 0x00020000);
+    f32x4 rx[XU], rw[WU];
     // weight staging: unit u is 16 bytes of output channel co0 + u / WQ; slots past the tile
     // duplicate earlier units, channels past K re-read the last valid channel (their products
     // land in accumulator columns that are never stored)
@@ -177,15 +180,76 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             // unit u of the chunk image goes to unit u of the LDS buffer
             const int u = (tid + i * NT) % PU;
             woff[i] = 4u * (uint32_t)(tile_n * nchunks * (BN * WS) + 4 * u);
-            wlds[i] = 4u * (uint32_t)(2 * patch_sz + 4 * u);
+            wlds[i] = 4u * (uint32_t)(NBUF * patch_sz + 4 * u);
         } else {
             const int u = (tid + i * NT) % (BN * WQ);
             const int co = u / WQ, kq = u - co * WQ;
             const int gco = co0 + co < p.K ? co0 + co : p.K - 1;
             woff[i] = 4u * (uint32_t)(gco * (p.C * RS9) + 4 * kq);
-            wlds[i] = 4u * (uint32_t)(2 * patch_sz + co * WS + 4 * kq);
+            wlds[i] = 4u * (uint32_t)(NBUF * patch_sz + co * WS + 4 * kq);
+        }
+        rw[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff[i], 0, 0));
+    }
+    // x staging.  A unit is (channel ci of the chunk, virtual row vr of the patch, quad j4 of the
+    // row).  Where a channel's units fit the work-group (row_groups > 0), a thread keeps ONE (vr, j4)
+    // and its slots walk the channels ci = cg, cg + row_groups, ...: image, input row and validity
+    // are worked out once per thread and a slot costs an add and a select.  Otherwise unit u = tid +
+    // i * NT: the first slot is decomposed by division, the others follow by adding the
+    // decomposition of NT with carries.  A slot whose unit lies past the patch repeats the thread's
+    // first one.
+    uint32_t xoff[XU], xlds[XU];
+    bool xvalid[XU];
+    if (g.row_groups) {
+        int cg = g.d_perc.div(tid);
+        const int ru = tid - cg * (g.VR * g.W4);
+        cg = cg < g.row_groups ? cg : 0;       // surplus threads repeat units of the first group
+        const int vr = g.d_w4.div(ru), j4 = ru - vr * g.W4;
+        const int v = v0 + vr;
+        const int n = g.d_hv.div(v), ih = v - n * g.HV - p.pad_h;
+        const bool valid = n < p.N && ih >= 0 && ih < p.H;
+        const uint32_t offc = 4u * (uint32_t)(n * p.xs[0] + cg * p.xs[1] + ih * p.xs[2] + 4 * j4);
+        const uint32_t ldsc = 4u * (uint32_t)(cg * P + vr * RSL + g.XC + 4 * j4);
+        const uint32_t step_off = 4u * (uint32_t)(g.row_groups * p.xs[1]), step_lds = 4u * (uint32_t)(g.row_groups * P);
+#pragma unroll
+        for (int i = 0; i < XU; ++i) {
+            const bool in = cg + i * g.row_groups < CK;
+            xvalid[i] = valid;
+            xoff[i] = valid ? (in ? offc + (uint32_t)i * step_off : offc) : 0u;
+            xlds[i] = in ? ldsc + (uint32_t)i * step_lds : ldsc;
+            rx[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)xoff[i], 0, 0));
+        }
+    } else {
+        int ci = 0, vr = 0, j4 = 0, ci0 = 0, vr0 = 0, j40 = 0;
+#pragma unroll
+        for (int i = 0; i < XU; ++i) {
+            if (i == 0) {
+                int u = tid;
+                u -= g.d_units.div(u) * g.n_units;
+                ci = g.d_perc.div(u);
+                const int rem = u - ci * (g.VR * g.W4);
+                vr = g.d_w4.div(rem);
+                j4 = rem - vr * g.W4;
+                ci0 = ci, vr0 = vr, j40 = j4;
+            } else {
+                j4 += g.st_j4;
+                int carry = j4 >= g.W4;
+                j4 -= carry ? g.W4 : 0;
+                vr += g.st_vr + carry;
+                carry = vr >= g.VR;
+                vr -= carry ? g.VR : 0;
+                ci += g.st_ci + carry;
+            }
+            const bool past = ci >= CK;
+            const int eci = past ? ci0 : ci, evr = past ? vr0 : vr, ej4 = past ? j40 : j4;
+            const int v = v0 + evr;
+            const int n = g.d_hv.div(v), ih = v - n * g.HV - p.pad_h;
+            xvalid[i] = n < p.N && ih >= 0 && ih < p.H;
+            xoff[i] = xvalid[i] ? 4u * (uint32_t)(n * p.xs[0] + eci * p.xs[1] + ih * p.xs[2] + 4 * ej4) : 0u;
+            xlds[i] = 4u * (uint32_t)(eci * P + evr * RSL + g.XC + 4 * ej4);
+            rx[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)xoff[i], 0, 0));
         }
     }
+    __builtin_amdgcn_sched_barrier(0);     // the loads stay here: the compiler would sink them to their first use
 
     // ---- per-lane operand addresses in LDS, bytes (the wave's share of the k-steps is folded in)
     uint32_t abase[WM_BLK];
@@ -202,7 +266,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     uint32_t bbase[WN_BLK];
 #pragma unroll
     for (int nb = 0; nb < WN_BLK; ++nb)
-        bbase[nb] = 4u * (uint32_t)(2 * patch_sz + ((wave_n * WN_BLK + nb) * 32 + r32) * WS + h * CPH * RS9 +
+        bbase[nb] = 4u * (uint32_t)(NBUF * patch_sz + ((wave_n * WN_BLK + nb) * 32 + r32) * WS + h * CPH * RS9 +
                                     ks * SPW);
 
     f32x16 acc[WM_BLK][WN_BLK];
@@ -213,15 +277,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
-    f32x4 rx[XU], rw[WU];
-
-    // staging unit j: global -> registers.  Buffer loads: the descriptor (base, extent) sits in
-    // scalar registers for the whole kernel, the lane supplies a 32-bit byte offset and the chunk
-    // a scalar one, so a load needs no vector ALU work for its address.
-    const __amdgpu_buffer_rsrc_t xrsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, (int)g.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(PACKED ? p.wpack : p.w), 0, (int)(PACKED ? g.wpack_bytes : g.w_bytes), 0x00020000);
+    // staging unit j of a later chunk: global -> registers
     auto side_load = [&](int j, uint32_t xchunk_b, uint32_t wchunk_b) {
         if (j < XU)
             rx[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)xoff[j], (int)xchunk_b, 0));
@@ -246,62 +302,143 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         }
     };
 
-#pragma unroll
-    for (int j = 0; j < NSIDE; ++j) side_load(j, 0u, 0u);
-    for (int idx = tid; idx < (2 * patch_sz) / 4; idx += NT)
+    for (int idx = tid; idx < (NBUF * patch_sz) / 4; idx += NT)
         reinterpret_cast<f32x4*>(smem)[idx] = zero4();
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NSIDE; ++j) side_store(j, 0, 0);
-    __syncthreads();
 
-    // One chunk: MFMAs on LDS buffer `buf`, staging of chunk cc+1 into the other buffer.
-    auto chunk = [&](int cc, auto buf_c) {
-        constexpr int buf = decltype(buf_c)::value;
-        // the chunk after the last one is the last one again: loaded and stored, never read
-        const int cn = cc + 1 < nchunks ? cc + 1 : cc;
-        const uint32_t xb = 4u * (uint32_t)cn * (uint32_t)(CK * p.xs[1]);     // byte offset of the chunk
-        const uint32_t wb = 4u * (uint32_t)cn * (uint32_t)(PACKED ? BN * WS : KC);
-        const int rd_a = 4 * buf * patch_sz, rd_b = 4 * buf * WTS_SZ;
-        const int st_a = 4 * (buf ^ 1) * patch_sz, st_b = 4 * (buf ^ 1) * WTS_SZ;
-
-        float a_cur[WM_BLK], b_cur[WN_BLK], a_nxt[WM_BLK], b_nxt[WN_BLK];
-        auto read_step = [&](int t, float* a, float* b) {
-            const int cl = t / RS9, tap = t % RS9;
-            const int offA = 4 * (cl * P + (tap / S_) * RSL + (tap % S_)) + rd_a;
+    if constexpr (NBUF == 3) {
+        // Ring of three staging buffers.  Chunk c is multiplied from buffer c % 3; meanwhile, in
+        // the first half of the chunk, the data of chunk c + 1 (requested during chunk c - 1) goes
+        // to buffer (c + 1) % 3, then comes the chunk's one barrier, then the requests for chunk
+        // c + 2.  A wave that has passed the barrier of chunk c knows that every wave has stored
+        // chunk c + 1 and is beyond chunk c - 1, so it may read buffer (c + 1) % 3 as soon as it is
+        // done with chunk c and overwrite buffer (c + 2) % 3 in the first half of chunk c + 1.  With
+        // two buffers the barrier has to stand at the end of a chunk, where every wave then waits
+        // with nothing queued on its matrix pipe for the first operands of the next chunk to come
+        // from LDS (about 260 cycles per chunk); here the barrier stands between two MFMAs whose
+        // operands are already in registers, and the first operands of the next chunk are read
+        // during the last k-step of this one.
+        // slots of a chunk: stores [ST0, LD0), requests for chunk c + 2 [LD0, LD0 + NSIDE), the
+        // barrier after slot BAR: GAP MFMAs behind the last store, so the stores have landed when the
+        // wave waits for them, and before the last k-step, which reads the next chunk's operands
+        constexpr int GAP = 4;
+        constexpr int BAR = SLOTS - NBLK - 1;
+        constexpr int LD0 = BAR + 1 - GAP, ST0 = LD0 - NSIDE;
+        static_assert(ST0 >= 0 && LD0 + NSIDE <= SLOTS, "a chunk has too few MFMAs for this schedule");
+        {
+            const int c1 = nchunks > 1 ? 1 : 0;
+            const uint32_t xb = 4u * (uint32_t)c1 * (uint32_t)(CK * p.xs[1]);
+            const uint32_t wb = 4u * (uint32_t)c1 * (uint32_t)(PACKED ? BN * WS : KC);
 #pragma unroll
-            for (int mb = 0; mb < WM_BLK; ++mb) a[mb] = *reinterpret_cast<const float*>(lds + abase[mb] + offA);
-#pragma unroll
-            for (int nb = 0; nb < WN_BLK; ++nb)
-                b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + rd_b);
-        };
-        read_step(0, a_cur, b_cur);
-#pragma unroll
-        for (int t = 0; t < SPW; ++t) {
-            // reads of step t+1 are issued before the MFMAs of step t: their latency hides
-            // behind those MFMAs instead of stalling the next ones
-            if (t + 1 < SPW) read_step(t + 1, a_nxt, b_nxt);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int mb = 0; mb < WM_BLK; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < WN_BLK; ++nb) {
-                    acc[mb][nb] = mfma32(a_cur[mb], b_cur[nb], acc[mb][nb]);
-                    const int slot = (t * WM_BLK + mb) * WN_BLK + nb;
-                    if (slot < NSIDE) side_load(slot, xb, wb);
-                    if (slot >= STORE0) side_store(slot - STORE0, st_a, st_b);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-            for (int mb = 0; mb < WM_BLK; ++mb) a_cur[mb] = a_nxt[mb];
-#pragma unroll
-            for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
+            for (int j = 0; j < NSIDE; ++j) side_load(j, xb, wb);     // chunk 1, stored during chunk 0
         }
         __syncthreads();
-    };
-    for (int cc = 0; cc < nchunks; cc += 2) {
-        chunk(cc, std::integral_constant<int, 0>{});
-        if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
+        float a_cur[WM_BLK], b_cur[WN_BLK], a_nxt[WM_BLK], b_nxt[WN_BLK];
+        // the third buffer may lie beyond the 64 KB an LDS instruction's immediate offset reaches:
+        // it gets address registers of its own rather than an addition per read
+        uint32_t abase2[WM_BLK];
+#pragma unroll
+        for (int mb = 0; mb < WM_BLK; ++mb) abase2[mb] = abase[mb] + 4u * (uint32_t)(2 * patch_sz);
+        auto read_step = [&](int t, int buf, float* a, float* b) {
+            const int cl = t / RS9, tap = t % RS9;
+            const int offA = 4 * (cl * P + (tap / S_) * RSL + (tap % S_)) + (buf == 1 ? 4 * patch_sz : 0);
+#pragma unroll
+            for (int mb = 0; mb < WM_BLK; ++mb)
+                a[mb] = *reinterpret_cast<const float*>(lds + (buf == 2 ? abase2[mb] : abase[mb]) + offA);
+#pragma unroll
+            for (int nb = 0; nb < WN_BLK; ++nb)
+                b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + 4 * buf * WTS_SZ);
+        };
+        read_step(0, 0, a_cur, b_cur);
+        auto chunk = [&](int cc, auto buf_c) {
+            constexpr int buf = decltype(buf_c)::value, nbuf = (buf + 1) % 3;
+            // chunks past the last one are the last one again: loaded and stored, never read
+            const int c2 = cc + 2 < nchunks ? cc + 2 : nchunks - 1;
+            const uint32_t xb = 4u * (uint32_t)c2 * (uint32_t)(CK * p.xs[1]);
+            const uint32_t wb = 4u * (uint32_t)c2 * (uint32_t)(PACKED ? BN * WS : KC);
+#pragma unroll
+            for (int t = 0; t < SPW; ++t) {
+                if (t + 1 < SPW)
+                    read_step(t + 1, buf, a_nxt, b_nxt);
+                else
+                    read_step(0, nbuf, a_nxt, b_nxt);          // first operands of the next chunk
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mb = 0; mb < WM_BLK; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < WN_BLK; ++nb) {
+                        acc[mb][nb] = mfma32(a_cur[mb], b_cur[nb], acc[mb][nb]);
+                        const int slot = (t * WM_BLK + mb) * WN_BLK + nb;
+                        if (slot >= ST0 && slot < LD0) side_store(slot - ST0, 4 * nbuf * patch_sz, 4 * nbuf * WTS_SZ);
+                        if (slot >= LD0 && slot < LD0 + NSIDE) side_load(slot - LD0, xb, wb);
+                        if (slot == BAR) __syncthreads();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                for (int mb = 0; mb < WM_BLK; ++mb) a_cur[mb] = a_nxt[mb];
+#pragma unroll
+                for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
+            }
+        };
+        for (int cc = 0; cc < nchunks; cc += 3) {
+            chunk(cc, std::integral_constant<int, 0>{});
+            if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
+            if (cc + 2 < nchunks) chunk(cc + 2, std::integral_constant<int, 2>{});
+        }
+        __syncthreads();        // the partial sums below go where the staging buffers are
+    } else {
+        __syncthreads();
+
+        // One chunk: MFMAs on LDS buffer `buf`, staging of chunk cc+1 into the other buffer.
+        auto chunk = [&](int cc, auto buf_c) {
+            constexpr int buf = decltype(buf_c)::value;
+            // the chunk after the last one is the last one again: loaded and stored, never read
+            const int cn = cc + 1 < nchunks ? cc + 1 : cc;
+            const uint32_t xb = 4u * (uint32_t)cn * (uint32_t)(CK * p.xs[1]);     // byte offset of the chunk
+            const uint32_t wb = 4u * (uint32_t)cn * (uint32_t)(PACKED ? BN * WS : KC);
+            const int rd_a = 4 * buf * patch_sz, rd_b = 4 * buf * WTS_SZ;
+            const int st_a = 4 * (buf ^ 1) * patch_sz, st_b = 4 * (buf ^ 1) * WTS_SZ;
+
+            float a_cur[WM_BLK], b_cur[WN_BLK], a_nxt[WM_BLK], b_nxt[WN_BLK];
+            auto read_step = [&](int t, float* a, float* b) {
+                const int cl = t / RS9, tap = t % RS9;
+                const int offA = 4 * (cl * P + (tap / S_) * RSL + (tap % S_)) + rd_a;
+#pragma unroll
+                for (int mb = 0; mb < WM_BLK; ++mb) a[mb] = *reinterpret_cast<const float*>(lds + abase[mb] + offA);
+#pragma unroll
+                for (int nb = 0; nb < WN_BLK; ++nb)
+                    b[nb] = *reinterpret_cast<const float*>(lds + bbase[nb] + 4 * t + rd_b);
+            };
+            read_step(0, a_cur, b_cur);
+#pragma unroll
+            for (int t = 0; t < SPW; ++t) {
+                // reads of step t+1 are issued before the MFMAs of step t: their latency hides
+                // behind those MFMAs instead of stalling the next ones
+                if (t + 1 < SPW) read_step(t + 1, a_nxt, b_nxt);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mb = 0; mb < WM_BLK; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < WN_BLK; ++nb) {
+                        acc[mb][nb] = mfma32(a_cur[mb], b_cur[nb], acc[mb][nb]);
+                        const int slot = (t * WM_BLK + mb) * WN_BLK + nb;
+                        if (slot < NSIDE) side_load(slot, xb, wb);
+                        if (slot >= STORE0) side_store(slot - STORE0, st_a, st_b);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                for (int mb = 0; mb < WM_BLK; ++mb) a_cur[mb] = a_nxt[mb];
+#pragma unroll
+                for (int nb = 0; nb < WN_BLK; ++nb) b_cur[nb] = b_nxt[nb];
+            }
+            __syncthreads();
+        };
+        for (int cc = 0; cc < nchunks; cc += 2) {
+            chunk(cc, std::integral_constant<int, 0>{});
+            if (cc + 1 < nchunks) chunk(cc + 1, std::integral_constant<int, 1>{});
+        }
     }
 
     // ---- Outputs whose quads of four pixels are 16 aligned bytes of y (every tuned shape): the
@@ -316,20 +453,9 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     //      39.2 us storing from the accumulator layout, 37.9 us with the runs, 36.5 us with the runs
     //      stored non-temporally (the 16-byte pieces stored non-temporally: 43.7 us).
     if (g.vec_store) {
-        f32x4* red = reinterpret_cast<f32x4*>(smem);
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) {
-            const f32x16& c = acc[b / WN_BLK][b % WN_BLK];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int q = 2 * v + h;
-                f32x4 t = {c[4 * v], c[4 * v + 1], c[4 * v + 2], c[4 * v + 3]};
-                red[((tile_wave * NBLK + b) * KSPLIT + ks) * 256 + q * 32 + (r32 ^ q)] = t;
-            }
-        }
-        __syncthreads();
         const int c8 = lane >> 3, q = lane & 7;
-        // batch-norm constants of the lane's four channels per channel block
+        // batch-norm constants of the lane's four channels per channel block, requested before the
+        // partials go to LDS so that they arrive behind that and the barrier
         float scale[WN_BLK][4], shift[WN_BLK][4];
         if (p.gamma) {
 #pragma unroll
@@ -347,32 +473,54 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
                     }
                 }
         }
+        f32x4* red = reinterpret_cast<f32x4*>(smem);
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) {
+            const f32x16& c = acc[b / WN_BLK][b % WN_BLK];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int qa = 2 * v + h;      // the quad these four accumulator registers are
+                f32x4 t = {c[4 * v], c[4 * v + 1], c[4 * v + 2], c[4 * v + 3]};
+                red[((tile_wave * NBLK + b) * KSPLIT + ks) * 256 + qa * 32 + (r32 ^ qa)] = t;
+            }
+        }
+        __syncthreads();
+        // an owned block: all its partial quads are requested from LDS before the first is used (one
+        // latency per block, not one per channel), then summed, scaled and stored
+        auto finish_block = [&](int b, auto with_bn) {
             const int mb = b / WN_BLK, nb = b % WN_BLK;
-            if (ks != b % KSPLIT) continue;
             const int mq = m0 + (wave_m * WM_BLK + mb) * 32 + 4 * q;
             const int mc = mq < g.Mtot ? mq : 0;
             const int n = g.d_ohow.div(mc), pix = mc - n * g.ohow;
             float* const yq = p.y + n * p.ys[0] + pix;
             const f32x4* blk = red + (tile_wave * NBLK + b) * KSPLIT * 256 + q * 32;
+            f32x4 part[4][KSPLIT];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int src = 0; src < KSPLIT; ++src) part[j][src] = blk[src * 256 + ((8 * j + c8) ^ q)];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int c = 8 * j + c8;
-                f32x4 v = blk[c ^ q];
+                f32x4 v = part[j][0];
 #pragma unroll
-                for (int src = 1; src < KSPLIT; ++src) {
-                    const f32x4 t = blk[src * 256 + (c ^ q)];
+                for (int src = 1; src < KSPLIT; ++src)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += t[e];
-                }
-                if (p.gamma) {
+                    for (int e = 0; e < 4; ++e) v[e] += part[j][src][e];
+                if (decltype(with_bn)::value) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = fmaxf(fmaf(v[e], scale[nb][j], shift[nb][j]), 0.f);
                 }
-                const int co = co0 + (wave_n * WN_BLK + nb) * 32 + c;
+                const int co = co0 + (wave_n * WN_BLK + nb) * 32 + 8 * j + c8;
                 if (mq < g.Mtot && co < p.K) stg4_nt(yq + co * p.ys[1], v);
             }
+        };
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            if (ks != b % KSPLIT) continue;
+            if (p.gamma)
+                finish_block(b, std::true_type{});
+            else
+                finish_block(b, std::false_type{});
         }
         return;
     }
@@ -513,6 +661,23 @@ struct Variant {
         g->P = g->VR * g->RSL;
         g->W4 = a.W / 4;
         g->n_units = CK * g->VR * g->W4;
+        {
+            const int per_c = g->VR * g->W4, rest = NT % per_c;
+            g->st_ci = NT / per_c;
+            g->st_vr = rest / g->W4;
+            g->st_j4 = rest % g->W4;
+            // one (row, quad) per thread where that needs no more slots than dealing the units out singly
+            g->slots = (g->n_units + NT - 1) / NT;
+            g->row_groups = 0;
+            if (per_c <= NT) {
+                const int groups = NT / per_c < CK ? NT / per_c : CK;
+                const int slots = (CK + groups - 1) / groups;
+                if (slots <= g->slots) {
+                    g->row_groups = groups;
+                    g->slots = slots;
+                }
+            }
+        }
         if (kMaxXU < 1 || g->n_units > kMaxXU * NT) return false;
         // virtual row numbers must stay below 2^31 for the fast division
         if ((int64_t)a.N * g->HV + g->VR >= ((int64_t)1 << 31)) return false;
@@ -549,26 +714,37 @@ struct Variant {
                 }
             }
         }
-        g->d_sub_n = make_fastdiv(g->xcd_n ? g->tiles_n / g->xcd_n : 1);
-        size_t floats = 2 * ((size_t)CK * g->P + (size_t)BN * WS);
-        // the k-split reduction reuses the staging memory: every wave's partial blocks
-        const size_t red = (size_t)KSPLIT * WAVES_M * WAVES_N * WM_BLK * WN_BLK * 64 * 16;
-        if (red > floats) floats = red;
-        *lds_bytes = sizeof(float) * floats;
+        g->sub_m = g->xcd_m ? g->tiles_m / g->xcd_m : 0;
+        g->sub_n = g->xcd_n ? g->tiles_n / g->xcd_n : 0;
+        g->xcd_n_shift = 0;
+        while (g->xcd_n && (1 << g->xcd_n_shift) < g->xcd_n) ++g->xcd_n_shift;
+        g->d_sub_n = make_fastdiv(g->xcd_n ? g->sub_n : 1);
+        g->d_tiles_m = make_fastdiv(g->tiles_m);
+        *lds_bytes = lds_bytes_for(*g, 2);
         return *lds_bytes <= 160 * 1024;
     }
 
-    template <int XU, int RSL_T, int P_T>
-    static hipError_t launch_inst(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    // LDS of a work-group with `nbuf` staging buffers
+    static size_t lds_bytes_for(const Geom& g, int nbuf)
     {
-        return a.wpack ? launch_as<XU, RSL_T, P_T, true>(a, g, lds_bytes, stream)
-                       : launch_as<XU, RSL_T, P_T, false>(a, g, lds_bytes, stream);
+        size_t floats = nbuf * ((size_t)CK * g.P + (size_t)BN * WS);
+        // the k-split reduction reuses the staging memory: every wave's partial blocks
+        const size_t red = (size_t)KSPLIT * WAVES_M * WAVES_N * WM_BLK * WN_BLK * 64 * 16;
+        if (red > floats) floats = red;
+        return sizeof(float) * floats;
     }
 
-    template <int XU, int RSL_T, int P_T, bool PACKED>
+    template <int XU, int RSL_T, int P_T, int NBUF = 2>
+    static hipError_t launch_inst(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
+    {
+        return a.wpack ? launch_as<XU, RSL_T, P_T, true, NBUF>(a, g, lds_bytes, stream)
+                       : launch_as<XU, RSL_T, P_T, false, NBUF>(a, g, lds_bytes, stream);
+    }
+
+    template <int XU, int RSL_T, int P_T, bool PACKED, int NBUF>
     static hipError_t launch_as(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
     {
-        auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T, PACKED>;
+        auto kern = conv_igemm_kernel<WM_BLK, WN_BLK, WAVES_M, WAVES_N, KSPLIT, R_, S_, CPH, XU, RSL_T, P_T, PACKED, NBUF>;
         if (lds_bytes > 64 * 1024) {
             static LdsLimit granted;
             hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_bytes, granted);
@@ -578,14 +754,16 @@ struct Variant {
         return launch_kernel(kern, grid, dim3(NT), lds_bytes, stream, a, g);
     }
 
-    static int units_per_thread(const Geom& g) { return (g.n_units + NT - 1) / NT; }
+    static int units_per_thread(const Geom& g) { return g.slots; }
 
     // Instantiation with the LDS geometry (row stride, plane stride) and the number of staging
-    // units per thread fixed at compile time; the caller has checked that g matches.
-    template <int XU, int RSL_T, int P_T>
+    // units per thread fixed at compile time; the caller has checked that g matches.  These run
+    // the ring of three staging buffers (every shape they are made for leaves room for it).
+    template <int XU, int RSL_T, int P_T, int NBUF = 2>
     static hipError_t launch_fixed(const ConvArgs& a, const Geom& g, size_t lds_bytes, hipStream_t stream)
     {
-        return launch_inst<XU, RSL_T, P_T>(a, g, lds_bytes, stream);
+        static_assert(NBUF * sizeof(float) * ((size_t)CK * P_T + (size_t)BN * WS) <= 160 * 1024, "LDS");
+        return launch_inst<XU, RSL_T, P_T, NBUF>(a, g, NBUF == 2 ? lds_bytes : lds_bytes_for(g, NBUF), stream);
     }
 
     // Any geometry: LDS strides are run-time values (address arithmetic stays in the loop).
