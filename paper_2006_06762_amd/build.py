@@ -25,12 +25,15 @@ FLAGS = [
 ]
 
 
-# Per-file flags.  The patch-staging convolution keeps its accumulators in ordinary vector registers
-# (it runs one wave per SIMD and fits): its prologue and epilogue then need no copies between the
-# two register files (measured 0.25-0.35 us per launch on the three benchmark convolutions; no
-# gain on the GEMM and attention kernels).
+# Per-file flags.  The convolution and GEMM kernels keep their MFMA accumulators in ordinary vector
+# registers instead of the accumulation registers: prologues and epilogues then need no copies
+# between the two register files.  Measured: 0.25-0.35 us per launch on the three benchmark
+# convolutions, 1-2 % on the general convolution kernels, 6-10 % on GEMMs of 512^3 x 16 and
+# 2048^3; no gain on the attention kernels, which are left alone.
 FILE_FLAGS = {
     "conv_igemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "conv_gather.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 
 

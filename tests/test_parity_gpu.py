@@ -260,6 +260,44 @@ def test_conv2d_pointwise_stream(anr, shape):
     assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
 
 
+RING_GEOMETRIES = [          # the layer geometries whose instantiations run the ring of three staging buffers
+    (4, 56, 56, 64, (1, 1)),     # 56x56 maps, stride 1: 224 x 64 tiles
+    (4, 28, 28, 32, (1, 1)),     # 28x28 maps, stride 1: 224 x 32 tiles
+    (4, 28, 28, 32, (2, 2)),     # 28x28 maps, stride 2
+]
+
+
+@pytest.mark.parametrize("geom", RING_GEOMETRIES, ids=str)
+@pytest.mark.parametrize("C", [8, 16, 24, 32, 40])
+def test_conv2d_patch_kernel_few_chunks(anr, geom, C):
+    """The tuned instantiations of the patch kernel keep three staging buffers in rotation, with chunk
+    c + 1 stored and chunk c + 2 requested while chunk c is multiplied: one to five chunks of eight
+    channels cover a reduction shorter than the ring, every buffer's first use and the first wrap-around.
+    Integer values bit for bit, unpacked and packed, then the fused epilogue within the bar."""
+    N, H, W, K, stride = geom
+    s = I.ConvShape(N, C, H, W, K, 3, 3, stride, (1, 1))
+    d = anr.conv_desc((s.N, s.C, s.H, s.W), s.K, 3, 3, s.stride, s.pad, route=1)
+    assert anr.conv2d_route(d).kernel == anr.ANR_CONV_KERNEL_PATCH
+    x, w = I.conv_inputs(s, 1600 + C, ints=True)
+    ref = oracle.conv2d(x, w, s.stride, s.pad)
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, route=1)
+    check_guard(buf)
+    assert_parity(y, ref, exact=True, what="patch kernel, %d chunks %s" % (C // 8, geom))
+    d, pack = anr.conv2d_pack_weights((s.N, s.C, s.H, s.W), dev(w), s.stride, s.pad, route=1)
+    y.fill_(CANARY)
+    anr.conv2d_packed(d, dev(x), pack, y)
+    check_guard(buf)
+    assert_parity(y, ref, exact=True, what="patch kernel packed, %d chunks %s" % (C // 8, geom))
+    x, w = I.conv_inputs(s, 1650 + C)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 1651 + C)
+    w = (w * 4).astype(np.float32)
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad, route=1)
+    check_guard(buf)
+    assert_parity(y, oracle.conv_bn_relu(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad),
+                  what="patch kernel ConvLayer, %d chunks %s" % (C // 8, geom))
+
+
 # ------------------------------------------------------------------ pre-packed weights
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
 def test_conv2d_packed_configs(anr, name):
