@@ -43,11 +43,19 @@
 // branch-free (spare staging slots duplicate a real unit, padding rows store
 // zeros): a load inside a divergent branch makes the compiler drain all
 // outstanding loads first, which serialises a chunk's memory latency.
-// One barrier per chunk.
+// One barrier per chunk: at its end with two staging buffers (run-time LDS
+// strides), a k-step before its end with the ring of three buffers that the
+// instantiations for fixed layer geometries use (described at the loop).
 //
-// The batch-norm scale/shift and ReLU of ConvLayer run on the accumulators in
-// the epilogue (Table 1, rule 4: fuse element-wise consumers into the tiled
-// node); results are written straight from registers, 16 bytes per lane.
+// Set-up order: the loads of the first chunk are issued as soon as their
+// offsets exist; operand addresses, accumulators and the zeroing of the padding
+// follow while they are in flight.
+//
+// The batch-norm scale/shift and ReLU of ConvLayer run on the summed partial
+// tiles in the epilogue (Table 1, rule 4: fuse element-wise consumers into the
+// tiled node); where four consecutive pixels are 16 aligned bytes of y, the
+// k-split reduction doubles as a transposition and results leave in 128-byte
+// runs, otherwise straight from the accumulator layout.
 #pragma once
 #include <type_traits>
 
@@ -323,7 +331,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
         // slots of a chunk: stores [ST0, LD0), requests for chunk c + 2 [LD0, LD0 + NSIDE), the
         // barrier after slot BAR: GAP MFMAs behind the last store, so the stores have landed when the
         // wave waits for them, and before the last k-step, which reads the next chunk's operands
-        constexpr int GAP = 4;
+        constexpr int GAP = NSIDE > 8 ? 8 : 4;    // measured: 8 pays with eleven stores to drain (stride 2: 69.7 -> 68.8 us), not with six or eight
         constexpr int BAR = SLOTS - NBLK - 1;
         constexpr int LD0 = BAR + 1 - GAP, ST0 = LD0 - NSIDE;
         static_assert(ST0 >= 0 && LD0 + NSIDE <= SLOTS, "a chunk has too few MFMAs for this schedule");
