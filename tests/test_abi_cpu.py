@@ -6,6 +6,7 @@ import os
 import re
 import subprocess
 
+import numpy as np
 import pytest
 
 from paper_2006_06762_amd import binding as B
@@ -389,6 +390,41 @@ def test_conv_route_packs_small_groups_of_pointwise_layers():
 def test_conv_route_beyond_32bit_offsets_is_the_direct_kernel():
     r = route((1, 2, 16400, 16400), 1, 3, 1, 1)[1]
     assert r.kernel == B.ANR_CONV_KERNEL_DIRECT and r.workspace_bytes == 0
+
+
+def test_conv_planning_random_descriptors():
+    """Host-side planning over a few thousand random layer descriptors, all three routes: every plan
+    names a kernel, a tile and a work-group count, the workspace query agrees with it, the pack size
+    is that of the weights or more, and forcing the general route never picks the patch kernel."""
+    g = np.random.Generator(np.random.PCG64(20060676))
+    kernels = {B.ANR_CONV_KERNEL_PATCH, B.ANR_CONV_KERNEL_GATHER, B.ANR_CONV_KERNEL_TAPS, B.ANR_CONV_KERNEL_BIGTAPS,
+               B.ANR_CONV_KERNEL_DIRECT, B.ANR_CONV_KERNEL_POINTWISE}
+    seen = set()
+    for i in range(3000):
+        R = int(g.choice([1, 3, 3, 3, 5, 7]))
+        groups = int(g.choice([1, 1, 1, 2, 4]))
+        C = groups * int(g.choice([1, 3, 4, 8, 16, 24, 32, 64, 96]))
+        K = groups * int(g.choice([1, 8, 16, 32, 48, 64, 100]))
+        H = int(g.choice([7, 8, 14, 16, 28, 30, 56, 57, 112]))
+        W = int(g.choice([7, 8, 12, 14, 16, 28, 36, 56, 60, 112, 224]))
+        N = int(g.choice([1, 2, 4, 16, 33]))
+        stride = int(g.choice([1, 1, 2]))
+        dil = int(g.choice([1, 1, 1, 2]))
+        pad = int(g.choice([0, R // 2, R // 2, R - 1]))
+        if (H + 2 * pad - dil * (R - 1) - 1) < 0 or (W + 2 * pad - dil * (R - 1) - 1) < 0:
+            continue
+        for rt in (B.ANR_CONV_ROUTE_AUTO, B.ANR_CONV_ROUTE_PATCH, B.ANR_CONV_ROUTE_GENERAL):
+            d = B.conv_desc((N, C, H, W), K, R, R, (stride, stride), (pad, pad), dil=(dil, dil), groups=groups, route=rt)
+            r = B.conv2d_route(d)
+            assert r.kernel in kernels, (i, rt)
+            assert r.tile_m > 0 and r.tile_n > 0 and r.work_groups > 0 and r.ksplit >= 1, (i, rt, r.kernel)
+            assert r.workspace_bytes == B.workspace_size(B.ANR_OP_CONV2D, d) == B.workspace_size(B.ANR_OP_CONV_BN_RELU, d)
+            assert (r.workspace_bytes > 0) == (r.ksplit > 1), (i, rt)
+            assert B.conv2d_packed_size(d) >= 4 * K * (C // groups) * R * R
+            if rt == B.ANR_CONV_ROUTE_GENERAL:
+                assert r.kernel != B.ANR_CONV_KERNEL_PATCH
+            seen.add(r.kernel)
+    assert {B.ANR_CONV_KERNEL_PATCH, B.ANR_CONV_KERNEL_GATHER, B.ANR_CONV_KERNEL_TAPS, B.ANR_CONV_KERNEL_POINTWISE} <= seen
 
 
 def test_conv_route_validation():
