@@ -111,7 +111,7 @@ void set_tile(const ConvArgs& a, Plan* g, int bm, int bn, int ks)
     // 3-4 % faster than one 16-byte piece per lane and channel; the 7 x 7 stem at batch 16, which writes
     // 51 MB: 7 %; partial tiles of a split reduction, whose workspace is padded and aligned: 1-2 %)
     g->tstore = (g->taps != 0 || (bm == 64 && bn == 64)) && g->nwg == 1 && (g->ksplit > 1 || g->vec_store);
-    g->rblocks = (g->Mpad / 4 * kReduceLanes + 255) / 256;
+    g->rblocks = (g->Mpad / 4 * reduce_lanes(g->ksplit) + 255) / 256;
     g->d_rblocks = make_fastdiv(g->rblocks);
 }
 
@@ -322,8 +322,13 @@ hipError_t launch_gather_plan(const ConvArgs& a, const Plan& g, hipStream_t stre
     else if (g.bm == 128) err = launch_tile<128, 64>(a, g, stream);
     else err = launch_tile<64, 64>(a, g, stream);
     if (err != hipSuccess || g.ksplit == 1) return err;
-    return launch_kernel(conv_splitk_reduce_kernel, dim3((unsigned)((int64_t)a.K * g.rblocks)), dim3(256), 0, stream,
-                         a, g);
+    const dim3 rgrid((unsigned)((int64_t)a.K * g.rblocks));
+    switch (reduce_lanes(g.ksplit)) {
+        case 8: return launch_kernel(conv_splitk_reduce_kernel<8>, rgrid, dim3(256), 0, stream, a, g);
+        case 4: return launch_kernel(conv_splitk_reduce_kernel<4>, rgrid, dim3(256), 0, stream, a, g);
+        case 2: return launch_kernel(conv_splitk_reduce_kernel<2>, rgrid, dim3(256), 0, stream, a, g);
+        default: return launch_kernel(conv_splitk_reduce_kernel<1>, rgrid, dim3(256), 0, stream, a, g);
+    }
 }
 
 }  // namespace anr

@@ -817,14 +817,19 @@ __global__ __launch_bounds__(256) void conv_bigtaps_kernel(const ConvArgs p, con
     store_tile<1, 1>(p, g, acc, split, tile_n, m0, cl0, cog, wm, wn, r32, h);
 }
 
-// Sums the ksplit partial tiles and runs the epilogue.  Eight lanes share one (output channel,
-// four consecutive pixels): lane j adds the partials of splits j, j + 8, ... (all its loads in
-// flight at once), then the eight sums are combined by a fixed shuffle tree, so the result does
-// not depend on scheduling.  One memory round trip however many splits there are.
-constexpr int kReduceLanes = 8;
+// Sums the ksplit partial tiles and runs the epilogue.  LANES lanes share one (output channel,
+// four consecutive pixels): lane j adds the partials of splits j, j + LANES, ... (all its loads in
+// flight at once, up to four per lane), then the sums are combined by a fixed shuffle tree, so
+// the result does not depend on scheduling.  One memory round trip however many splits there
+// are; with few splits fewer lanes per quad, so that a launch is not eight times the waves its
+// loads need (five splits of 14x14x256 at batch 16: 25088 waves of one load per lane with eight
+// lanes, 6272 of three with two).
+inline int reduce_lanes(int ksplit) { return ksplit > 16 ? 8 : ksplit > 8 ? 4 : ksplit > 4 ? 2 : 1; }
 
+template <int LANES>
 __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs p, const Plan g)
 {
+    constexpr int kReduceLanes = LANES;
     // a work-group stays inside one output channel (blocks_per_co of them per channel), so the
     // channel, its workspace column and its batch-norm constants are scalar work
     const int co = g.d_rblocks.div((int)blockIdx.x);
@@ -838,20 +843,21 @@ __global__ __launch_bounds__(256) void conv_splitk_reduce_kernel(const ConvArgs 
     const float* src = p.ws + ((int64_t)grp * g.tiles_ng * g.bn + (co - grp * g.Kg)) * g.Mpad + (mq < g.Mpad ? mq : 0);
     const int64_t step = (int64_t)g.Kpad * g.Mpad;
     f32x4 v = zero4();
-    int s = sub;
-    for (; s + 3 * kReduceLanes < g.ksplit; s += 4 * kReduceLanes) {
+    // four loads in flight per round, none under a branch: a round's surplus slots re-read the
+    // lane's first split (LANES <= ksplit, so that one exists) and are left out of the sum
+    for (int s = sub; s < g.ksplit; s += 4 * kReduceLanes) {
         f32x4 u[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) u[i] = ldg4(src + (s + i * kReduceLanes) * step);
+        for (int i = 0; i < 4; ++i) {
+            const int idx = s + i * kReduceLanes;
+            u[i] = ldg4(src + (idx < g.ksplit ? idx : sub) * step);
+        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            const bool in = s + i * kReduceLanes < g.ksplit;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] += u[i][r];
-    }
-    for (; s < g.ksplit; s += kReduceLanes) {
-        const f32x4 u = ldg4(src + s * step);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] += u[r];
+            for (int r = 0; r < 4; ++r) v[r] += in ? u[i][r] : 0.f;
+        }
     }
 #pragma unroll
     for (int o = 1; o < kReduceLanes; o <<= 1)
