@@ -120,14 +120,14 @@ int64_t packed_floats(const ConvArgs& a, const IgemmPlan& p, int* bn, int* ck)
 }
 
 // Writes the pack's weights part in the patch kernel's order: for channel tile t and chunk q the
-// LDS image of the tile's BN channels, KC = CK * 9 weights each in OIHW order followed by the two
+// LDS image of the tile's BN channels, KC = CK * 9 weights each in OIHW order followed by the four
 // floats of padding of an LDS row; channels past K are zero.  One thread per float.
 __global__ __launch_bounds__(256) void conv_pack_patch_kernel(const float* __restrict__ w, float* __restrict__ out,
                                                               int K, int C, int bn, int ck, int64_t total)
 {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
-    const int kc = ck * 9, ws = kc + 2, nchunks = C / ck;
+    const int kc = ck * 9, ws = kc + 4, nchunks = C / ck;
     const int j = (int)(idx % ws);
     int64_t t = idx / ws;
     const int col = (int)(t % bn);

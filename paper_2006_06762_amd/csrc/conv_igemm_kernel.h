@@ -85,7 +85,7 @@ struct Geom {
     int tiles_m, tiles_n, xcd_m, xcd_n;
     int sub_m, sub_n, xcd_n_shift;   // tiles_m / xcd_m, tiles_n / xcd_n, log2(xcd_n)
     uint32_t x_bytes, w_bytes;   // extents of the x view and of w, for the buffer descriptors
-    uint32_t wpack_bytes;        // extent of the packed weights: tiles_n * chunks * BN * (KC + 2) floats
+    uint32_t wpack_bytes;        // extent of the packed weights: tiles_n * chunks * BN * (KC + 4) floats
     FastDiv d_sub_n;            // divisor tiles_n / xcd_n
     FastDiv d_tiles_m;
 };
@@ -106,7 +106,11 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
     constexpr int RS9 = R_ * S_;
     constexpr int CK = 2 * CPH;           // channels per chunk
     constexpr int KC = CK * RS9;          // reduction length per chunk
-    constexpr int WS = KC + 2;            // LDS stride of one output channel's weights
+    // LDS stride of one output channel's weights: a multiple of four floats, so that a staging unit
+    // is ONE 16-byte LDS store (with KC + 2, two 8-byte ones: conflict-free operand reads, but 0.5-1.3 us
+    // slower per benchmark layer -- the operand reads of 32 consecutive rows now fall on 16 banks,
+    // which costs nothing measurable)
+    constexpr int WS = KC + 4;
     constexpr int STEPS = CPH * RS9;      // MFMA k-steps per chunk (all waves of a tile together)
     constexpr int SPW = STEPS / KSPLIT;   // k-steps per chunk of one wave
     constexpr int WQ = KC / 4;
@@ -298,15 +302,7 @@ void conv_igemm_kernel(const ConvArgs p, const Geom g)
             if (xvalid[j]) *reinterpret_cast<f32x4*>(lds + xlds[j] + xbuf_b) = rx[j];
         } else {
             const f32x4 v = rw[j - XU];
-            if (PACKED) {
-                *reinterpret_cast<f32x4*>(lds + wlds[j - XU] + wbuf_b) = v;
-            } else {
-                // a channel's row in LDS starts 8-byte aligned only (stride KC + 2)
-                f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
-                f32x2* dst = reinterpret_cast<f32x2*>(lds + wlds[j - XU] + wbuf_b);
-                dst[0] = lo;
-                dst[1] = hi;
-            }
+            *reinterpret_cast<f32x4*>(lds + wlds[j - XU] + wbuf_b) = v;
         }
     };
 
@@ -642,13 +638,13 @@ struct Variant {
     static constexpr int NT = 64 * WAVES_M * WAVES_N * KSPLIT;
     static constexpr int BM = 32 * WM_BLK * WAVES_M, BN = 32 * WN_BLK * WAVES_N;
     static constexpr int CK = 2 * CPH;
-    static constexpr int WS = CK * R_ * S_ + 2;
+    static constexpr int WS = CK * R_ * S_ + 4;
     // staging units per thread the main loop can hide: half of a wave's MFMAs per chunk carry one
     static constexpr int WU = (BN * (CK * R_ * S_ / 4) + NT - 1) / NT;
     static constexpr int SLOTS = (CPH * R_ * S_ / KSPLIT) * WM_BLK * WN_BLK;
     static constexpr int kMaxXU = (SLOTS / 2 - WU) < kMaxUnits ? (SLOTS / 2 - WU) : kMaxUnits;
 
-    // Floats of the packed weights: per channel tile and chunk one LDS image of BN rows of KC + 2.
+    // Floats of the packed weights: per channel tile and chunk one LDS image of BN rows of KC + 4.
     static int64_t packed_floats(const ConvArgs& a)
     {
         return (int64_t)((a.K + BN - 1) / BN) * (a.C / CK) * BN * WS;

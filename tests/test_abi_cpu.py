@@ -161,12 +161,12 @@ def test_packed_weights_size_and_validation():
     lib = B.raw()
     n = ctypes.c_size_t(0)
     # patch-kernel plan: scale/shift block (2K floats rounded up to 64) + per channel tile and chunk an
-    # LDS image of 32 rows x (8 channels x 9 taps + 2) floats for the 28x28 ConvLayer shape
+    # LDS image of 32 rows x (8 channels x 9 taps + 4) floats for the 28x28 ConvLayer shape
     d = B.conv_desc((16, 128, 28, 28), 128, 3, 3, (1, 1), (1, 1))
-    assert B.conv2d_packed_size(d) == 4 * (256 + 4 * 16 * 32 * (8 * 9 + 2))
+    assert B.conv2d_packed_size(d) == 4 * (256 + 4 * 16 * 32 * (8 * 9 + 4))
     # the stride-2 layer: chunks of 8 channels, 16 channel tiles of 32
     d2 = B.conv_desc((16, 256, 28, 28), 512, 3, 3, (2, 2), (1, 1))
-    assert B.conv2d_packed_size(d2) == 4 * (1024 + 16 * 32 * 32 * (8 * 9 + 2))
+    assert B.conv2d_packed_size(d2) == 4 * (1024 + 16 * 32 * 32 * (8 * 9 + 4))
     # any other plan keeps OIHW order
     d3 = B.conv_desc((1, 3, 224, 224), 64, 7, 7, (2, 2), (3, 3))
     assert B.conv2d_packed_size(d3) == 4 * (128 + 64 * 3 * 49)
