@@ -333,8 +333,9 @@ def test_conv_route_by_kernel_size_and_channels():
         d, r = route(shape, Kout, R, 1, pad)
         assert r.kernel == K.ANR_CONV_KERNEL_TAPS and (r.tile_m, r.tile_n) == (64, 64)
         assert r.workspace_bytes == K.workspace_size(K.ANR_OP_CONV2D, d)
-    # pointwise layers with few channels on dense images: the streaming kernel (no workspace); not with
-    # more channels, groups, a stride, too few tiles, or when the general family is ruled out by route 1
+    # pointwise layers with few channels on dense images, grouped or not: the streaming kernel (no
+    # workspace); not with more channels, groups that are not whole 16-byte units of a weight row, a
+    # stride, too few tiles, or when the general family is ruled out by route 1
     d, r = route((16, 64, 56, 56), 64, 1)
     assert r.kernel == K.ANR_CONV_KERNEL_POINTWISE and r.work_groups == 16 * 49 and r.workspace_bytes == 0
     assert K.workspace_size(K.ANR_OP_CONV2D, d) == 0
@@ -342,7 +343,8 @@ def test_conv_route_by_kernel_size_and_channels():
     assert route((16, 256, 28, 28), 64, 1)[1].kernel == K.ANR_CONV_KERNEL_TAPS
     assert route((16, 64, 56, 56), 64, 1, stride=2)[1].kernel == K.ANR_CONV_KERNEL_TAPS
     assert route((1, 64, 56, 56), 64, 1)[1].kernel == K.ANR_CONV_KERNEL_TAPS
-    assert route((16, 64, 56, 56), 64, 1, groups=4)[1].kernel == K.ANR_CONV_KERNEL_TAPS
+    assert route((16, 64, 56, 56), 64, 1, groups=4)[1].kernel == K.ANR_CONV_KERNEL_POINTWISE
+    assert route((16, 96, 56, 56), 96, 1, groups=16)[1].kernel != K.ANR_CONV_KERNEL_POINTWISE      # 6 channels per group
     assert route((16, 64, 56, 56), 64, 1, dil=2)[1].kernel == K.ANR_CONV_KERNEL_POINTWISE      # one tap: dilation is moot
     # 7x7 stem and 5x5: one channel per chunk
     assert route((16, 3, 224, 224), 64, 7, 2, 3)[1].kernel == K.ANR_CONV_KERNEL_BIGTAPS
@@ -375,9 +377,9 @@ def test_conv_route_wave_groups_and_split():
 
 
 def test_conv_route_packs_small_groups_of_pointwise_layers():
-    # 56x56, 64 -> 64, 1x1, 4 groups of 16 channels: the four groups share one 64-wide column tile
-    # (784 work-groups, as for the ungrouped layer) instead of taking a quarter-filled tile each
-    r = route((16, 64, 56, 56), 64, 1, groups=4)[1]
+    # 56x56, 256 -> 64, 1x1, 4 groups of 16 output channels: the four groups share one 64-wide column
+    # tile (784 work-groups, as for an ungrouped layer) instead of taking a quarter-filled tile each
+    r = route((16, 256, 56, 56), 64, 1, groups=4)[1]
     assert (r.kernel, r.tile_n, r.ksplit, r.wave_groups, r.work_groups) == (B.ANR_CONV_KERNEL_TAPS, 64, 1, 1, 784)
     # 32 groups of 4 output channels: two packs of 16 groups
     assert route((16, 256, 28, 28), 128, 1, groups=32)[1].work_groups == 196 * 2

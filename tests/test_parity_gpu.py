@@ -298,6 +298,33 @@ def test_conv2d_patch_kernel_few_chunks(anr, geom, C):
                   what="patch kernel ConvLayer, %d chunks %s" % (C // 8, geom))
 
 
+GROUPED_POINTWISE_SHAPES = [     # grouped 1x1 layers the streaming kernel takes: a block-diagonal weight tile
+    I.ConvShape(16, 64, 56, 56, 64, 1, 1, (1, 1), (0, 0), (1, 1), 4),     # the GRP layer of Appendix C at batch 16
+    I.ConvShape(20, 128, 30, 30, 96, 1, 1, (1, 1), (0, 0), (1, 1), 8),     # 16 -> 12 channels per group, two channel tiles, ragged pixels
+    I.ConvShape(64, 32, 14, 14, 64, 1, 1, (1, 1), (0, 0), (1, 1), 8),      # 4 -> 8 channels per group: one 16-byte unit per row
+    I.ConvShape(20, 96, 26, 34, 48, 1, 1, (1, 1), (0, 0), (1, 1), 2),      # channels past K in the tile
+]
+
+
+@pytest.mark.parametrize("shape", GROUPED_POINTWISE_SHAPES, ids=str)
+def test_conv2d_pointwise_stream_groups(anr, shape):
+    s = shape
+    d = anr.conv_desc((s.N, s.C, s.H, s.W), s.K, 1, 1, groups=s.groups)
+    assert anr.conv2d_route(d).kernel == anr.ANR_CONV_KERNEL_POINTWISE
+    x, w = I.conv_inputs(s, 1520, ints=True)
+    buf, y = guarded((s.N, s.K, s.OH, s.OW))
+    anr.conv2d(dev(x), dev(w), y, s.stride, s.pad, groups=s.groups)
+    check_guard(buf)
+    assert_parity(y, oracle.conv2d_general(x, w, s.stride, s.pad, s.dil, s.groups), exact=True, what="grouped pointwise %s" % (s,))
+    x, w = I.conv_inputs(s, 1521)
+    gamma, beta, mean, var = I.bn_inputs(s.K, 1522)
+    w = (w * 4).astype(np.float32)
+    anr.conv_bn_relu(dev(x), dev(w), dev(gamma), dev(beta), dev(mean), dev(var), I.BN_EPS, y, s.stride, s.pad, groups=s.groups)
+    check_guard(buf)
+    ref = oracle.conv_bn_relu_general(x, w, gamma, beta, mean, var, I.BN_EPS, s.stride, s.pad, s.dil, s.groups)
+    assert_parity(y, ref, what="grouped pointwise ConvLayer %s" % (s,))
+
+
 # ------------------------------------------------------------------ pre-packed weights
 @pytest.mark.parametrize("name", ["C2D", "C2D_S2"])
 def test_conv2d_packed_configs(anr, name):
