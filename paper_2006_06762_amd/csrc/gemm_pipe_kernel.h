@@ -11,7 +11,9 @@
 // reduction index past K gets an offset beyond the descriptor's extent, which loads zero
 // without a branch.
 //
-// LDS: A (and B of the A.B^T form) row-major in k with a row stride of 34 floats, read two k
+// LDS: A (and B of the A.B^T form) row-major in k with a row stride of 36 floats (a staging unit is
+// then one 16-byte store; with 34, conflict-free 8-byte operand reads but two stores per unit,
+// 1024^3 x16 and 4096^3 ran 3 % slower), read two k
 // at a time (8-byte reads, half-wave h takes k = 4j + 2h, 4j + 2h + 1: any order is a valid
 // reduction order as long as both operands use it); B of the A.B form stays k-major as it is
 // in memory, row stride BN + 16 floats (rows 4j + 2h of the two half-waves then fall into
@@ -26,7 +28,7 @@ namespace anr {
 namespace gpipe {
 
 constexpr int KC = 32;
-constexpr int WS = KC + 2;
+constexpr int WS = KC + 4;       // LDS row stride of the k-contiguous tiles: a staging unit is one 16-byte store
 constexpr uint32_t kOutOfRange = 0x80000000u;
 
 template <int BM, int BN, bool NT>
@@ -145,10 +147,7 @@ __global__ __launch_bounds__(256 * NWG) void gemm_pipe_kernel(const GemmArgs p, 
         constexpr int count = sizeof(reg) / sizeof(f32x4);
 #pragma unroll
         for (int j = 0; j < count; ++j) {
-            f32x2* dst = reinterpret_cast<f32x2*>(&tile[((tid >> 3) + 32 * j) * WS + ak]);
-            const f32x2 lo = {reg[j][0], reg[j][1]}, hi = {reg[j][2], reg[j][3]};
-            dst[0] = lo;
-            dst[1] = hi;
+            *reinterpret_cast<f32x4*>(&tile[((tid >> 3) + 32 * j) * WS + ak]) = reg[j];
         }
     };
     auto store_chunk = [&](int buf, auto set_c) {
@@ -251,7 +250,9 @@ __global__ __launch_bounds__(256 * NWG) void gemm_pipe_kernel(const GemmArgs p, 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + (wm * MB + mb) * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (row < M) C[(int64_t)row * p.ldc + col] = acc[mb][nb][r];
+                // 32 lanes write one whole 128-byte run of a row; C is not read again (non-temporal:
+                // no dirty lines left for the end of the kernel)
+                if (row < M) __builtin_nontemporal_store(acc[mb][nb][r], &C[(int64_t)row * p.ldc + col]);
             }
         }
 }
